@@ -1,0 +1,209 @@
+"""CPU oracle for the Flux Attention inference hot path.  TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, fp64 NumPy: the definitions written out, no tiling, no online
+softmax, no fusion.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this file; the product (the HIP
+library and its Python binding) never does, and nothing here imports the
+product.
+
+What it follows (paper sections / equations):
+
+* Full Attention, Eq. (1) of Sec. 2.1: ``O_r = Softmax(Q K^T) V`` per head,
+  causal, with the usual 1/sqrt(d) scale the paper omits "for clarity".
+* Sparse Attention, Eq. (2) of Sec. 2.1: the same softmax over a subset of the
+  history.  The subset is the streaming one of Sec. 4.1 / App. C.3: the first
+  ``n_sink`` positions plus the ``window`` most recent positions (the query's
+  own position counts as the most recent).
+* Grouped-query attention: query head ``h`` reads KV head ``h // (Hq // Hkv)``.
+* Layer Router, Sec. 3.1: prefix/suffix pooling of the first and last ``pool``
+  token rows (App. C.1: 100 + 100) into one mean vector, Context Encoder
+  ``Linear -> SiLU``, Router Head ``Linear`` to two logits ``(pi_FA, pi_SA)``,
+  hard decision by argmax with ``r_hard = 0`` meaning SA.
+* Route once in prefill, reuse the decision for every decode step, Sec. 3.3.
+* Model Sparsity Ratio, Eq. (3) of Sec. 2.3, at layer granularity.
+
+Conventions: ``mode`` 1 = FA, 0 = SA (the paper's ``r_hard``).  All arrays are
+float64; bf16 inputs are widened exactly by ``bf16_to_f64`` first.  Positions
+are absolute and 0-based; the ``n_q`` queries of a call are the last ``n_q``
+positions of the ``n_kv`` cached ones.
+
+Pins (tests/test_oracle_pins.py): closed-form visible counts, window >= length
+equals FA, rows of P sum to one, constant-V and constant-K special cases, shift
+invariance, brute-force enumeration on 8-token cases, a textbook dense
+formula, GQA by head repetition, decode == last prefill row, a hand-computed
+router, argmax flip and tie.  No function here is parity-unpinned.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+FA, SA = 1, 0
+
+
+def bf16_to_f64(bits) -> np.ndarray:
+    """Exact widening of bf16 bit patterns (uint16) to float64."""
+    b = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return b.view(np.float32).astype(np.float64)
+
+
+# --------------------------------------------------------------------------- mask
+
+def visible(i, j, mode: int, n_sink: int, window: int):
+    """Whether query position ``i`` attends key position ``j`` (broadcasts).
+
+    FA: every ``j <= i``.  SA: ``j <= i`` and (``j`` is one of the first
+    ``n_sink`` positions or ``j`` is among the ``window`` most recent, i.e.
+    ``i - j < window``).
+    """
+    i = np.asarray(i)
+    j = np.asarray(j)
+    causal = j <= i
+    if mode == FA:
+        return causal
+    return causal & ((j < n_sink) | (i - j < window))
+
+
+def mask_matrix(n_q: int, n_kv: int, mode: int, n_sink: int, window: int) -> np.ndarray:
+    """Explicit boolean mask [n_q, n_kv]; row r is query position ``n_kv - n_q + r``."""
+    i = (n_kv - n_q + np.arange(n_q))[:, None]
+    j = np.arange(n_kv)[None, :]
+    return visible(i, j, mode, n_sink, window)
+
+
+# --------------------------------------------------------------------------- attention
+
+def softmax_rows(s: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """Row-wise softmax of ``s`` restricted to ``mask`` (max-subtracted, fp64)."""
+    s = np.where(mask, s, -np.inf)
+    m = s.max(axis=-1, keepdims=True)
+    p = np.where(mask, np.exp(s - m), 0.0)
+    return p / p.sum(axis=-1, keepdims=True)
+
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mode: int, n_sink: int, window: int,
+              scale: float | None = None, return_probs: bool = False):
+    """One sequence, one layer, explicit mask matrix.
+
+    q [n_q, Hq, D], k and v [n_kv, Hkv, D] (fp64).  Returns out [n_q, Hq, D]
+    (and P [Hq, n_q, n_kv] if asked).
+    """
+    n_q, hq, d = q.shape
+    n_kv, hkv, _ = k.shape
+    assert hq % hkv == 0 and n_q <= n_kv
+    g = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    mask = mask_matrix(n_q, n_kv, mode, n_sink, window)
+    out = np.empty((n_q, hq, d), dtype=np.float64)
+    probs = np.empty((hq, n_q, n_kv), dtype=np.float64) if return_probs else None
+    for h in range(hq):
+        kh = k[:, h // g, :]
+        vh = v[:, h // g, :]
+        s = scale * (q[:, h, :] @ kh.T)
+        p = softmax_rows(s, mask)
+        out[:, h, :] = p @ vh
+        if return_probs:
+            probs[h] = p
+    return (out, probs) if return_probs else out
+
+
+def attention_row(q_row: np.ndarray, k: np.ndarray, v: np.ndarray, i: int, mode: int, n_sink: int,
+                  window: int, scale: float | None = None) -> np.ndarray:
+    """One query position ``i`` of one KV-head group, predicate evaluated along the row.
+
+    q_row [G, D] (the G query heads sharing this KV head), k and v [>= i+1, D].
+    Returns [G, D].  Same definition as ``attention``; used where the mask
+    matrix would not fit.
+    """
+    d = q_row.shape[-1]
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    j = np.arange(i + 1)
+    keep = visible(i, j, mode, n_sink, window)
+    kk = k[: i + 1][keep]
+    vv = v[: i + 1][keep]
+    s = scale * (q_row @ kk.T)                        # [G, n_visible]
+    s = s - s.max(axis=-1, keepdims=True)
+    p = np.exp(s)
+    p = p / p.sum(axis=-1, keepdims=True)
+    return p @ vv
+
+
+class KVCache:
+    """One layer's contiguous K/V history for a ragged batch (lists of fp64 arrays)."""
+
+    def __init__(self, batch: int, n_kv_heads: int, head_dim: int):
+        self.k = [np.zeros((0, n_kv_heads, head_dim)) for _ in range(batch)]
+        self.v = [np.zeros((0, n_kv_heads, head_dim)) for _ in range(batch)]
+
+    def append(self, b: int, k_new: np.ndarray, v_new: np.ndarray) -> None:
+        self.k[b] = np.concatenate([self.k[b], k_new], axis=0)
+        self.v[b] = np.concatenate([self.v[b], v_new], axis=0)
+
+    def length(self, b: int) -> int:
+        return self.k[b].shape[0]
+
+
+def prefill(cache: KVCache, q_list, k_list, v_list, modes, n_sink: int, window: int, scale=None):
+    """Append each sequence's new K/V rows, then attend with its new queries (Sec. 3.3).
+
+    ``modes[b]`` is that sequence's cached decision for this layer.
+    """
+    outs = []
+    for b, (q, k, v) in enumerate(zip(q_list, k_list, v_list)):
+        cache.append(b, k, v)
+        outs.append(attention(q, cache.k[b], cache.v[b], int(modes[b]), n_sink, window, scale))
+    return outs
+
+
+def decode_step(cache: KVCache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, modes,
+                n_sink: int, window: int, scale=None) -> np.ndarray:
+    """One autoregressive step: q [B, Hq, D], k_new/v_new [B, Hkv, D] -> out [B, Hq, D]."""
+    out = np.empty_like(q)
+    for b in range(q.shape[0]):
+        cache.append(b, k_new[b][None], v_new[b][None])
+        out[b] = attention(q[b][None], cache.k[b], cache.v[b], int(modes[b]), n_sink, window, scale)[0]
+    return out
+
+
+# --------------------------------------------------------------------------- router
+
+def pooled_rows(n_rows: int, pool: int) -> np.ndarray:
+    """Indices of the token rows that enter the pooling (Sec. 3.1, App. C.1).
+
+    The first ``pool`` and the last ``pool`` rows, each row once; every row if
+    the two stretches meet or overlap, or if ``pool`` is 0 (the "Full" setting
+    of App. D.2).
+    """
+    if pool <= 0 or n_rows <= 2 * pool:
+        return np.arange(n_rows)
+    return np.concatenate([np.arange(pool), np.arange(n_rows - pool, n_rows)])
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def router(x: np.ndarray, pool: int, w1: np.ndarray, b1, w2: np.ndarray, b2):
+    """Layer Router for one sequence.
+
+    x [S, hidden]; w1 [inner, hidden]; w2 [2, inner]; biases or None.
+    Returns (logits [2] = (pi_FA, pi_SA), mode) with mode 1 = FA when
+    ``pi_FA >= pi_SA`` (argmax, first index wins a tie), else 0 = SA.
+    """
+    p = x[pooled_rows(x.shape[0], pool)].mean(axis=0)
+    h = w1 @ p
+    if b1 is not None:
+        h = h + b1
+    h = silu(h)
+    logits = w2 @ h
+    if b2 is not None:
+        logits = logits + b2
+    mode = FA if int(np.argmax(logits)) == 0 else SA
+    return logits, mode
+
+
+def model_sparsity_ratio(modes) -> float:
+    """Eq. (3) at layer granularity: the fraction of (layer, sequence) slots routed to SA."""
+    modes = np.asarray(modes)
+    return float(np.mean(modes == SA))

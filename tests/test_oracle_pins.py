@@ -1,0 +1,284 @@
+"""Pins for the CPU oracle: closed forms, invariants, special cases and brute force.
+
+Each test is chosen so that a plausible mistake in oracle/flux_oracle.py (a
+dropped term, an off-by-one in the window, a transposed operand, a wrong GQA
+group, a missing scale) fails it.  Nothing here touches the GPU.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import flux_oracle as O
+
+FA, SA = O.FA, O.SA
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ----------------------------------------------------------------------------- mask
+
+def closed_form_visible(i, n_sink, window):
+    """Keys seen by SA row i: the window part plus the sinks that lie before the window."""
+    return min(i + 1, window) + max(0, min(n_sink, i + 1 - window))
+
+
+@pytest.mark.parametrize("n,n_sink,window", [(40, 0, 1), (40, 3, 5), (64, 16, 16), (50, 7, 64), (33, 40, 4)])
+def test_visible_count_closed_form(n, n_sink, window):
+    m = O.mask_matrix(n, n, SA, n_sink, window)
+    for i in range(n):
+        assert m[i].sum() == closed_form_visible(i, n_sink, window), i
+    # never anything from the future, always the query's own position
+    assert not np.triu(m, 1).any()
+    assert m.diagonal().all()
+
+
+def test_visible_pair_totals_config_shapes():
+    # Tiny config: S 512, 16 sinks, window 128 (values derived by hand from the closed form)
+    m = O.mask_matrix(512, 512, SA, 16, 128)
+    assert int(m.sum()) == 63432
+    assert int(O.mask_matrix(512, 512, FA, 16, 128).sum()) == 131328
+    # Stack-prefill config: S 32768, 128 sinks, window 4096, counted row block by row block
+    total_sa = total_fa = 0
+    n = 32768
+    j = np.arange(n)[None, :]
+    for r0 in range(0, n, 2048):
+        i = np.arange(r0, r0 + 2048)[:, None]
+        total_sa += int(O.visible(i, j, SA, 128, 4096).sum())
+        total_fa += int(O.visible(i, j, FA, 128, 4096).sum())
+    assert total_sa == 129_493_056
+    assert total_fa == 536_887_296
+
+
+def test_query_rows_are_the_last_positions():
+    # 3 queries over 10 cached positions: rows are positions 7, 8, 9
+    m = O.mask_matrix(3, 10, SA, 2, 3)
+    expect = np.zeros((3, 10), bool)
+    for r, i in enumerate((7, 8, 9)):
+        for j in range(10):
+            expect[r, j] = j <= i and (j < 2 or i - j < 3)
+    assert (m == expect).all()
+
+
+# ----------------------------------------------------------------------------- attention
+
+def make_qkv(seed, n_q, n_kv, hq, hkv, d):
+    r = rng(seed)
+    return (r.standard_normal((n_q, hq, d)), r.standard_normal((n_kv, hkv, d)),
+            r.standard_normal((n_kv, hkv, d)))
+
+
+def test_sa_with_window_covering_sequence_is_fa_bit_for_bit():
+    q, k, v = make_qkv(1, 48, 48, 4, 2, 8)
+    fa = O.attention(q, k, v, FA, 0, 0)
+    assert np.array_equal(O.attention(q, k, v, SA, 0, 48), fa)
+    assert np.array_equal(O.attention(q, k, v, SA, 5, 4096), fa)
+    assert np.array_equal(O.attention(q, k, v, SA, 48, 1), fa)      # sinks alone cover it
+
+
+def test_window_one_no_sinks_returns_own_value():
+    q, k, v = make_qkv(2, 20, 20, 4, 2, 8)
+    out = O.attention(q, k, v, SA, 0, 1)
+    for h in range(4):
+        assert np.allclose(out[:, h], v[:, h // 2], atol=0, rtol=0)
+
+
+def test_probability_rows_sum_to_one_and_respect_mask():
+    q, k, v = make_qkv(3, 30, 30, 2, 1, 4)
+    for mode in (FA, SA):
+        _, p = O.attention(q, k, v, mode, 3, 6, return_probs=True)
+        assert np.abs(p.sum(-1) - 1).max() < 1e-15
+        m = O.mask_matrix(30, 30, mode, 3, 6)
+        assert (p[:, ~m] == 0).all() and (p[:, m] > 0).all()
+
+
+def test_constant_values_and_first_row():
+    q, k, v = make_qkv(4, 16, 16, 4, 4, 8)
+    ones = np.ones_like(v)
+    for mode in (FA, SA):
+        assert np.abs(O.attention(q, k, ones, mode, 2, 4) - 1).max() < 1e-15
+        out = O.attention(q, k, v, mode, 2, 4)
+        assert np.array_equal(out[0], v[0])                   # row 0 sees only key 0
+
+
+def test_identical_keys_give_plain_mean_of_visible_values():
+    q, k, v = make_qkv(5, 24, 24, 2, 1, 4)
+    k[:] = k[0]
+    out = O.attention(q, k, v, SA, 2, 5)
+    m = O.mask_matrix(24, 24, SA, 2, 5)
+    for i in range(24):
+        assert np.allclose(out[i, 0], v[m[i], 0].mean(0), atol=1e-14)
+        assert np.allclose(out[i, 1], v[m[i], 0].mean(0), atol=1e-14)
+
+
+def test_shift_invariance_of_scores():
+    # add the same vector u to every key: each score of row i moves by scale * q_i.u, the same
+    # for all keys of the row, so O is unchanged
+    q, k, v = make_qkv(6, 12, 12, 2, 2, 8)
+    u = rng(60).standard_normal(8)
+    a = O.attention(q, k, v, FA, 0, 0)
+    b = O.attention(q, k + u, v, FA, 0, 0)
+    assert np.abs(a - b).max() < 1e-12
+
+
+def brute_force(q, k, v, mode, n_sink, window):
+    """Independent enumeration in pure-Python loops, no max-subtraction, own mask predicate."""
+    n_q, hq, d = q.shape
+    n_kv, hkv, _ = k.shape
+    group = hq // hkv
+    out = [[[0.0] * d for _ in range(hq)] for _ in range(n_q)]
+    for r in range(n_q):
+        i = n_kv - n_q + r
+        for h in range(hq):
+            kvh = h // group
+            weights = {}
+            for j in range(n_kv):
+                if j > i:
+                    continue
+                if mode == SA and not (j < n_sink or (i - j) <= window - 1):
+                    continue
+                dot = 0.0
+                for t in range(d):
+                    dot += q[r, h, t] * k[j, kvh, t]
+                weights[j] = math.exp(dot / math.sqrt(d))
+            z = sum(weights.values())
+            for j, w in weights.items():
+                for t in range(d):
+                    out[r][h][t] += w / z * v[j, kvh, t]
+    return np.array(out)
+
+
+@pytest.mark.parametrize("mode,n_sink,window", [(FA, 0, 0), (SA, 2, 3), (SA, 0, 2), (SA, 1, 1), (SA, 3, 8)])
+def test_brute_force_eight_tokens(mode, n_sink, window):
+    q, k, v = make_qkv(7, 8, 8, 2, 1, 4)
+    assert np.abs(O.attention(q, k, v, mode, n_sink, window) - brute_force(q, k, v, mode, n_sink, window)).max() < 1e-12
+    # chunked: 3 new queries over 8 cached positions
+    assert np.abs(O.attention(q[5:], k, v, mode, n_sink, window)
+                  - brute_force(q[5:], k, v, mode, n_sink, window)).max() < 1e-12
+
+
+def test_row_form_matches_matrix_form_and_brute_force():
+    q, k, v = make_qkv(8, 8, 8, 4, 2, 4)
+    ref = brute_force(q, k, v, SA, 2, 3)
+    for i in range(8):
+        for kvh in range(2):
+            row = O.attention_row(q[i, 2 * kvh:2 * kvh + 2], k[:, kvh], v[:, kvh], i, SA, 2, 3)
+            assert np.abs(row - ref[i, 2 * kvh:2 * kvh + 2]).max() < 1e-12
+
+
+def test_textbook_dense_formula_no_gqa():
+    # FA with one KV head per query head is softmax(Q K^T / sqrt(d) + causal) V
+    q, k, v = make_qkv(9, 32, 32, 3, 3, 16)
+    out = O.attention(q, k, v, FA, 0, 0)
+    for h in range(3):
+        s = q[:, h] @ k[:, h].T / np.sqrt(16.0)
+        s = s + np.triu(np.full((32, 32), -np.inf), 1)
+        e = np.exp(s - s.max(1, keepdims=True))
+        ref = (e / e.sum(1, keepdims=True)) @ v[:, h]
+        assert np.abs(out[:, h] - ref).max() < 1e-13
+
+
+def test_explicit_scale_is_used():
+    q, k, v = make_qkv(10, 8, 8, 2, 2, 4)
+    a = O.attention(q, k, v, FA, 0, 0, scale=0.5)          # 1/sqrt(4): the default
+    assert np.array_equal(a, O.attention(q, k, v, FA, 0, 0))
+    assert np.abs(a - O.attention(q, k, v, FA, 0, 0, scale=1.0)).max() > 1e-3
+    assert np.abs(O.attention(2 * q, k, v, FA, 0, 0, scale=0.25) - a).max() < 1e-13
+
+
+def test_gqa_equals_repeated_kv_heads():
+    q, k, v = make_qkv(11, 16, 16, 6, 2, 8)
+    a = O.attention(q, k, v, SA, 2, 5)
+    b = O.attention(q, np.repeat(k, 3, axis=1), np.repeat(v, 3, axis=1), SA, 2, 5)
+    assert np.array_equal(a, b)
+    # and the group order is h // G, not h % G
+    c = O.attention(q, np.tile(k, (1, 3, 1)), np.tile(v, (1, 3, 1)), SA, 2, 5)
+    assert np.abs(a - c).max() > 1e-3
+
+
+def test_decode_equals_last_prefill_row():
+    n, hq, hkv, d = 20, 4, 2, 8
+    q, k, v = make_qkv(12, n, n, hq, hkv, d)
+    for mode in (FA, SA):
+        full = O.attention(q, k, v, mode, 2, 4)
+        cache = O.KVCache(1, hkv, d)
+        cache.append(0, k[:10], v[:10])
+        for t in range(10, n):
+            out = O.decode_step(cache, q[t][None], k[t][None], v[t][None], [mode], 2, 4)
+            assert np.abs(out[0] - full[t]).max() < 1e-14
+        assert cache.length(0) == n
+
+
+def test_prefill_ragged_batch_and_chunks():
+    hq, hkv, d = 2, 1, 4
+    lens = [5, 9]
+    data = [make_qkv(20 + b, n, n, hq, hkv, d) for b, n in enumerate(lens)]
+    cache = O.KVCache(2, hkv, d)
+    # two chunks per sequence must equal one shot
+    outs1 = O.prefill(cache, [x[0][:3] for x in data], [x[1][:3] for x in data], [x[2][:3] for x in data], [FA, SA], 1, 2)
+    outs2 = O.prefill(cache, [x[0][3:] for x in data], [x[1][3:] for x in data], [x[2][3:] for x in data], [FA, SA], 1, 2)
+    for b, mode in enumerate([FA, SA]):
+        qq, kk, vv = data[b]
+        whole = O.attention(qq, kk, vv, mode, 1, 2)
+        assert np.abs(np.concatenate([outs1[b], outs2[b]]) - whole).max() < 1e-14
+
+
+# ----------------------------------------------------------------------------- router
+
+def test_pooled_rows():
+    assert list(O.pooled_rows(10, 2)) == [0, 1, 8, 9]
+    assert list(O.pooled_rows(4, 2)) == [0, 1, 2, 3]         # stretches meet: every row once
+    assert list(O.pooled_rows(3, 2)) == [0, 1, 2]            # stretches overlap: every row once
+    assert list(O.pooled_rows(5, 0)) == [0, 1, 2, 3, 4]      # pool 0 = whole sequence
+    assert list(O.pooled_rows(5, 2)) == [0, 1, 3, 4]
+
+
+def test_router_hand_computation():
+    # S 6, pool 2 -> rows 0, 1, 4, 5; the middle rows must not matter
+    x = np.array([[1, 2, 3, 4], [3, 2, 1, 0], [100, -50, 7, 9], [-3, 8, 1e3, 2], [1, 0, 1, 0], [3, 4, -1, 8]], float)
+    # pooled mean by hand: [8/4, 8/4, 4/4, 12/4] = [2, 2, 1, 3]
+    w1 = np.array([[1, -1, 2, 0], [0.5, 0, -1, 0.5]])        # W1 p = [2, 1.5]
+    b1 = np.array([-1, 0.5])                                 # pre-activation [1, 2]
+    w2 = np.array([[1, 2], [3, -1]])
+    b2 = np.array([0.25, -0.5])
+    silu1 = 0.7310585786300049                               # 1 * sigmoid(1)
+    silu2 = 2 * 0.8807970779778823                           # 2 * sigmoid(2)
+    pi_fa = 1 * silu1 + 2 * silu2 + 0.25
+    pi_sa = 3 * silu1 - 1 * silu2 - 0.5
+    logits, mode = O.router(x, 2, w1, b1, w2, b2)
+    assert abs(logits[0] - pi_fa) < 1e-12 and abs(logits[1] - pi_sa) < 1e-12
+    assert abs(logits[0] - 4.504246890541535) < 1e-12 and abs(logits[1] - (-0.06841842006575)) < 1e-12
+    assert mode == FA
+    # swapping the two head rows flips the decision: r_hard = 0 <=> SA
+    logits2, mode2 = O.router(x, 2, w1, b1, w2[::-1], b2[::-1])
+    assert np.allclose(logits2, logits[::-1], atol=0) and mode2 == SA
+    # no biases
+    l3, _ = O.router(x, 2, w1, None, w2, None)
+    h = np.array([2 / (1 + math.exp(-2)), 1.5 / (1 + math.exp(-1.5))])
+    assert np.abs(l3 - w2 @ h).max() < 1e-12
+    # whole-sequence pooling sees the middle rows
+    l4, _ = O.router(x, 0, w1, b1, w2, b2)
+    assert abs(l4[0] - logits[0]) > 1e-3
+
+
+def test_router_tie_goes_to_fa():
+    x = rng(30).standard_normal((7, 4))
+    w1 = rng(31).standard_normal((3, 4))
+    logits, mode = O.router(x, 2, w1, None, np.zeros((2, 3)), None)
+    assert logits[0] == logits[1] == 0 and mode == FA
+
+
+def test_model_sparsity_ratio():
+    assert O.model_sparsity_ratio([FA, SA, FA, SA]) == 0.5
+    assert O.model_sparsity_ratio([[FA, FA], [SA, FA]]) == 0.25
+    assert O.model_sparsity_ratio([FA] * 4) == 0.0
+
+
+def test_bf16_widening_exact():
+    bits = np.array([0x3F80, 0xBF80, 0x4000, 0x3DCD, 0x0000, 0x7F7F], dtype=np.uint16)
+    vals = O.bf16_to_f64(bits)
+    assert vals[0] == 1.0 and vals[1] == -1.0 and vals[2] == 2.0 and vals[4] == 0.0
+    assert vals[3] == 0.10009765625                      # 0x3DCD = 1.6015625 * 2**-4
+    assert vals[5] == (2 - 2 ** -7) * 2.0 ** 127

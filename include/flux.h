@@ -1,0 +1,146 @@
+/*
+ * flux.h - C ABI of the Flux Attention inference hot path for AMD MI355X (gfx950).
+ *
+ * The path: a per-layer Layer Router turns the prompt's boundary tokens into a hard
+ * Full-Attention / Sparse-Attention decision (paper Sec. 3.1), the decision is cached
+ * (Sec. 3.3), and each layer then runs causal grouped-query Full Attention (Eq. 1) or
+ * Sparse Attention (Eq. 2; the streaming variant of Sec. 4.1 / App. C.3: sink tokens plus a
+ * causal local window) over ONE contiguous bf16 KV cache, in prefill and in decode.
+ *
+ * General rules
+ *  - Every pointer is a raw address.  "dev" = device memory of the context's GPU, "host" =
+ *    ordinary host memory.  The caller owns every tensor and the stream; the library owns only
+ *    the workspace inside flux_ctx and never allocates in the hot calls.
+ *  - All calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default
+ *    stream) and never synchronise, except flux_create, flux_destroy, flux_last_device_status.
+ *  - Return value: 0 = FLUX_OK, negative = error.  Everything that can be checked from host
+ *    arguments is checked before any launch.  What only the device can see (a cache that would
+ *    overflow) is clamped so that no access leaves the buffers, and recorded in a sticky status
+ *    word readable with flux_last_device_status.
+ *  - mode bytes: 1 = FA, 0 = SA (the paper's r_hard; "r_hard = 0 executes SA", Sec. 3.1).
+ *  - bf16 tensors are 16-bit brain floats; their base addresses and all strides must be
+ *    multiples of 8 elements (16 bytes).  head_dim must be 64 or 128.
+ *  - Results are deterministic: same inputs and same shapes give bit-identical outputs.
+ *  - Calls that share one flux_ctx must be ordered on one stream (they share its workspace).
+ */
+#ifndef FLUX_H_
+#define FLUX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  FLUX_OK = 0,
+  FLUX_EINVAL = -1,      /* null pointer, bad head ratio, unsupported head_dim, negative size,
+                            misaligned pointer or stride */
+  FLUX_ECAPACITY = -2,   /* growth known on the host exceeds the cache capacity */
+  FLUX_EWORKSPACE = -3,  /* the context's workspace is too small for this call */
+  FLUX_EHIP = -4,        /* a HIP runtime call failed; text via flux_strerror */
+  FLUX_ENOMEM = -5       /* allocation failed in flux_create */
+};
+
+/* Bits of the sticky device status word. */
+enum {
+  FLUX_DEV_KV_OVERFLOW = 1,   /* flux_kv_append dropped rows that did not fit `capacity` */
+  FLUX_DEV_BAD_LENGTH = 2     /* a kv_len / cu_seqlens value was inconsistent and was clamped */
+};
+
+typedef struct flux_ctx flux_ctx;   /* opaque; owns ONLY its device workspace */
+
+/* Attention shape and the SA pattern of one call.
+ * SA visibility (Eq. 2 with the streaming subset): key j is seen by query position i iff
+ * j <= i and (j < n_sink or i - j < window); the query's own position counts inside the window.
+ * FA (Eq. 1): every j <= i.  Query head h reads KV head h / (n_q_heads / n_kv_heads). */
+typedef struct {
+  int32_t n_q_heads, n_kv_heads, head_dim;
+  int32_t n_sink, window;
+  float softmax_scale;      /* 0 => 1/sqrt(head_dim) (the scale Eq. 1 leaves out "for clarity") */
+  int32_t out_dtype;        /* 0 = bf16, 1 = fp32 */
+} flux_attn_cfg;
+
+/* One LAYER's KV cache, caller-owned: element (b, h, t, d) of K is
+ * k[b*stride_b + h*stride_h + t*stride_t + d], d contiguous, same strides for V. */
+typedef struct {
+  void* k;                  /* dev bf16 */
+  void* v;                  /* dev bf16 */
+  int64_t stride_b, stride_h, stride_t;   /* in elements */
+  int32_t* kv_len;          /* dev int32[batch]: valid positions per sequence */
+  int32_t batch, capacity;  /* capacity = positions per sequence the buffers can hold */
+} flux_kv_cache;
+
+/* Create a context on `device` with a workspace of `workspace_bytes` (0 = a default that covers
+ * batch*heads up to 256 and contexts up to 1M positions).  Synchronous.  The context may only
+ * be used with that device current. */
+int flux_create(flux_ctx** out, int device, size_t workspace_bytes);
+int flux_destroy(flux_ctx* ctx);
+
+/* Static text for an error code; for FLUX_EHIP the text of the last HIP error seen. */
+const char* flux_strerror(int code);
+
+/* Bytes of workspace flux_attn_decode needs for this shape (pure host arithmetic;
+ * prefill, router and append need less than 64 KiB).  0 on invalid arguments. */
+size_t flux_workspace_needed(const flux_attn_cfg* cfg, int batch, int max_kv_len);
+
+/* Waits for `stream`, returns the sticky device status bits (>= 0) and clears them. */
+int flux_last_device_status(flux_ctx* ctx, void* stream);
+
+/* Layer Router, hard-routing inference form (Sec. 3.1 "Architecture and Feature Extraction"
+ * and "Deterministic Inference via Hard Routing"; pooling of the first and last 100 tokens,
+ * App. C.1).  For each of the `batch` sequences packed in x (rows cu_seqlens[b] ..
+ * cu_seqlens[b+1]-1, each `hidden` wide):
+ *   p      = mean of the first `pool` and last `pool` rows (every row once if the sequence has
+ *            at most 2*pool rows, or if pool == 0)                         fp32
+ *   h      = SiLU(w1 p + b1)                                               fp32
+ *   logits = w2 h + b2 = (pi_FA, pi_SA)                                    fp32
+ *   mode   = 1 (FA) if pi_FA >= pi_SA else 0 (SA)       (argmax; a tie goes to index 0 = FA)
+ * x dev bf16 [T, hidden]; cu_seqlens dev int32 [batch+1]; w1 dev bf16 [inner, hidden];
+ * b1 dev bf16 [inner] or NULL; w2 dev bf16 [2, inner]; b2 dev bf16 [2] or NULL;
+ * mode_out dev uint8 [batch]; logits_out dev fp32 [batch, 2] or NULL.
+ * hidden must be a multiple of 8 and at most 16384, inner a multiple of 8 and at most 4096.
+ * Cost does not depend on the sequence length when pool > 0. */
+int flux_router(flux_ctx* ctx, const void* x, const int32_t* cu_seqlens, int batch, int hidden,
+                int pool, const void* w1, const void* b1, const void* w2, const void* b2, int inner,
+                uint8_t* mode_out, float* logits_out, void* stream);
+
+/* Append new K/V rows to the tail of each sequence's cache (the cache every later step of
+ * Sec. 3.3 reads).  k_new, v_new: dev bf16 [total_new, n_kv_heads, head_dim], rows of sequence b
+ * are cu_new[b] .. cu_new[b+1]-1 (dev int32 [batch+1]).  Row r of sequence b goes to position
+ * kv_len[b] + r; afterwards kv_len[b] += rows of b.  `total_new` and `max_new` (the largest
+ * per-sequence row count) are host values; max_new > capacity gives FLUX_ECAPACITY.  Rows that
+ * would pass `capacity` on the device are dropped and FLUX_DEV_KV_OVERFLOW is raised. */
+int flux_kv_append(flux_ctx* ctx, const flux_kv_cache* cache, int n_kv_heads, int head_dim,
+                   const void* k_new, const void* v_new, const int32_t* cu_new, int total_new,
+                   int max_new, void* stream);
+
+/* Prefill attention of one layer (Eq. 1 / Eq. 2, routed per sequence by `mode`, Sec. 3.3).
+ * q dev bf16 [T, n_q_heads, head_dim], rows of sequence b are cu_q[b] .. cu_q[b+1]-1 (dev int32
+ * [batch+1]).  The n_q(b) queries of sequence b are the LAST n_q(b) positions of its cache:
+ * query row r sits at position kv_len[b] - n_q(b) + r (append first, then attend; a chunk of a
+ * longer prompt and a whole prompt are the same call).  mode dev uint8 [batch].
+ * out dev [T, n_q_heads, head_dim] in cfg->out_dtype.  max_q_len, max_kv_len: host upper bounds
+ * on n_q(b) and kv_len[b] (they size the launch; larger than needed is valid, smaller truncates
+ * nothing: rows beyond max_q_len are not computed).  SA tiles that the mask hides are skipped,
+ * not masked. */
+int flux_attn_prefill(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const int32_t* cu_q,
+                      int max_q_len, int max_kv_len, const flux_kv_cache* cache,
+                      const uint8_t* mode, void* out, void* stream);
+
+/* Decode attention of one layer: one query per sequence at position kv_len[b]-1 (append first).
+ * q dev bf16 [batch, n_q_heads, head_dim]; out dev [batch, n_q_heads, head_dim].
+ * FA streams all kv_len[b] cached rows; SA reads only rows [0, n_sink) and
+ * [kv_len[b]-window, kv_len[b]) and never touches the rest (App. B.3).
+ * max_kv_len: host upper bound on the number of keys any sequence of this call ATTENDS TO; the
+ * largest kv_len[b] is always valid.  A caller that has read the cached mask back once and knows
+ * every sequence of this layer is SA may pass min(max kv_len, n_sink + window), which sizes the
+ * launch for the sparse case. */
+int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int max_kv_len,
+                     const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLUX_H_ */

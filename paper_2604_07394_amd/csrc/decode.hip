@@ -1,0 +1,336 @@
+// flux_attn_decode: split-K streaming attention for one query row per sequence (Eq. 1 / Eq. 2 with
+// one query; the decode step of Sec. 3.3 / App. B.3).
+//
+// Decode is bound by reading the K and V rows of the cache once from HBM.  The work of one
+// (sequence, KV head) pair is cut into chunks of the VISIBLE key list (FA: all positions; SA: the
+// sinks followed by the window tail, so the hidden middle of the cache is never addressed).  One
+// 256-thread workgroup owns one chunk and serves all query heads of the GQA group at once, so every
+// K/V row is fetched exactly once per step.
+//
+// Per wave, 32 keys at a time:
+//   S^T[key][q]  = K[key][:] . Q[q][:]       4 (D=128) MFMA 16x16x32 bf16 per 16 keys; the A operand
+//                                            (8 consecutive d of one key row per lane) is loaded
+//                                            straight from global memory, 64 contiguous bytes per row
+//                                            and instruction
+//   online softmax in the MFMA accumulator layout (one query per lane column, 4 keys per lane)
+//   O^T[d][q]   += V^T[d][key] . P^T[key][q] the P operand is the accumulator layout itself; the
+//                                            V operand needs keys along the lane's registers, so V
+//                                            rows are staged in wave-private LDS and read back with
+//                                            the transposing LDS read
+// The four waves keep private (m, l, O) and are merged through LDS at the end; the chunk's
+// unnormalised result goes to the workspace and a second small kernel merges the chunks in a fixed
+// order (deterministic, no float atomics).
+#include "flux_internal.h"
+
+namespace flux {
+
+struct DecodeArgs {
+  const __bf16* q;        // [B, Hq, D]
+  const __bf16* k;
+  const __bf16* v;
+  int64_t stride_b, stride_h, stride_t;   // elements
+  const int32_t* kv_len;
+  const uint8_t* mode;
+  int capacity;
+  int hq, hkv, group;     // group = hq / hkv
+  int qblocks;            // ceil(group / 16)
+  int n_sink, window;
+  int chunk, n_chunks;
+  float scale_log2;       // softmax scale * log2(e)
+  float* partials;        // [B, Hq, n_chunks, D + 2]
+};
+
+// number of keys sequence b attends to, and whether the sparse list (sinks + tail) applies
+__device__ __forceinline__ int visible_len(int n, int md, int n_sink, int window, bool& sparse) {
+  sparse = (md == 0) && (n > n_sink + window);
+  return sparse ? n_sink + window : n;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
+  constexpr int KC = D / 32;          // MFMA k-steps over the head dimension
+  constexpr int DB = D / 16;          // 16-wide output blocks over the head dimension
+  constexpr int VL = D / 16;          // 16-byte V loads per lane per 32-key block
+  constexpr int CPR = D / 8;          // 16-byte chunks per row
+  constexpr int VROW = D + 8;         // padded LDS row (elements)
+  constexpr int RED = D + 2;
+
+  __shared__ __attribute__((aligned(16))) char smem[4 * 32 * VROW * 2];
+
+  const int tid = threadIdx.x;
+  const int w = tid >> 6, l = tid & 63;
+  const int g = l >> 4, n = l & 15;
+  const int ci = blockIdx.x;
+  const int kvh = blockIdx.y / a.qblocks;
+  const int qb = blockIdx.y % a.qblocks;
+  const int b = blockIdx.z;
+
+  int len = a.kv_len[b];
+  len = len < 0 ? 0 : (len > a.capacity ? a.capacity : len);
+  bool sparse;
+  const int n_vis = visible_len(len, a.mode[b], a.n_sink, a.window, sparse);
+  const int c0 = ci * a.chunk;
+  if (c0 >= n_vis) return;                                  // uniform for the whole workgroup
+  const int c1 = min(c0 + a.chunk, n_vis);
+  const int tail0 = len - a.window - a.n_sink;              // list index p >= n_sink maps to key p + tail0
+
+  const __bf16* kbase = a.k + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
+  const __bf16* vbase = a.v + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
+
+  // ---- Q operand: lane (n, g) holds d = 32*kc + 8*g .. +7 of query head kvh*group + 16*qb + n
+  const int qh = 16 * qb + n;
+  bf16x8 qf[KC];
+  {
+    const u32x4 zero = {0, 0, 0, 0};
+    const __bf16* qrow = a.q + ((int64_t)b * a.hq + (int64_t)kvh * a.group + (qh < a.group ? qh : 0)) * D;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      u32x4 t = *(const u32x4*)(qrow + 32 * kc + 8 * g);
+      qf[kc] = __builtin_bit_cast(bf16x8, qh < a.group ? t : zero);
+    }
+  }
+
+  auto key_of = [&](int p) -> int64_t {
+    p = p < c1 ? p : c1 - 1;                                // keep every address inside the chunk
+    return (sparse && p >= a.n_sink) ? (int64_t)p + tail0 : (int64_t)p;
+  };
+
+  u32x4 kreg[2][KC], vreg[VL];
+  auto load_block = [&](int p0) {
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      const __bf16* row = kbase + key_of(p0 + 16 * sb + n) * a.stride_t;
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = *(const u32x4*)(row + 32 * kc + 8 * g);
+    }
+#pragma unroll
+    for (int i = 0; i < VL; ++i) {
+      const int e = i * 64 + l;
+      const __bf16* row = vbase + key_of(p0 + e / CPR) * a.stride_t;
+      vreg[i] = *(const u32x4*)(row + (e % CPR) * 8);
+    }
+  };
+
+  FLUX_LDS __bf16* vs = (FLUX_LDS __bf16*)smem + w * 32 * VROW;
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 o[DB];
+#pragma unroll
+  for (int i = 0; i < DB; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  int p0 = c0 + 32 * w;
+  if (p0 < c1) load_block(p0);
+  while (p0 < c1) {
+    // ---- stage this block's V rows in LDS and take K into MFMA operands
+#pragma unroll
+    for (int i = 0; i < VL; ++i) {
+      const int e = i * 64 + l;
+      *(FLUX_LDS u32x4*)(vs + (e / CPR) * VROW + (e % CPR) * 8) = vreg[i];
+    }
+    bf16x8 kf[2][KC];
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) kf[sb][kc] = __builtin_bit_cast(bf16x8, kreg[sb][kc]);
+    const int pnext = p0 + 128;
+    if (pnext < c1) load_block(pnext);                      // prefetch while computing
+
+    // ---- scores: s[sb][i] is key p0 + 16*sb + 4*g + i against query n
+    f32x4 s[2];
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      s[sb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc)
+        s[sb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[sb][kc], qf[kc], s[sb], 0, 0, 0);
+    }
+    if (p0 + 32 > c1) {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (p0 + 16 * sb + 4 * g + i >= c1) s[sb][i] = -INFINITY;
+    }
+    // ---- online softmax (row maximum over the 4 lane groups of this query)
+    float mloc = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                       fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+    const float m_new = fmaxf(m_run, mloc);                 // finite: the block holds a valid key
+    const float alpha = fast_exp2((m_run - m_new) * a.scale_log2);
+    const float mneg = -m_new * a.scale_log2;
+    m_run = m_new;
+    uint32_t pk[4];
+    float psum = 0.f;
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      const float p0f = fast_exp2(__builtin_fmaf(s[sb][0], a.scale_log2, mneg));
+      const float p1f = fast_exp2(__builtin_fmaf(s[sb][1], a.scale_log2, mneg));
+      const float p2f = fast_exp2(__builtin_fmaf(s[sb][2], a.scale_log2, mneg));
+      const float p3f = fast_exp2(__builtin_fmaf(s[sb][3], a.scale_log2, mneg));
+      pk[2 * sb] = pack_bf16(p0f, p1f);
+      pk[2 * sb + 1] = pack_bf16(p2f, p3f);
+      // the denominator sums the same rounded weights the numerator uses
+      psum += (bf16_lo(pk[2 * sb]) + bf16_hi(pk[2 * sb])) + (bf16_lo(pk[2 * sb + 1]) + bf16_hi(pk[2 * sb + 1]));
+    }
+    l_run = l_run * alpha + psum;
+    const bf16x8 pf = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      o[db] *= alpha;
+      FLUX_LDS __bf16* src = vs + (4 * g + (n >> 2)) * VROW + 16 * db + 4 * (n & 3);
+      const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)src);
+      const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)(src + 16 * VROW));
+      const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o[db], 0, 0, 0);
+    }
+    p0 = pnext;
+  }
+
+  // ---- merge the four waves through LDS: red[w][n][0..D-1] = O, [D] = m, [D+1] = l
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  __syncthreads();                                          // every wave is done with its V staging
+  FLUX_LDS float* red = (FLUX_LDS float*)smem;
+  static_assert(4 * 16 * RED * 4 <= 4 * 32 * VROW * 2, "merge buffer must fit the staging buffer");
+  {
+    FLUX_LDS float* mine = red + (w * 16 + n) * RED;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mine[16 * db + 4 * g + i] = o[db][i];
+    if (g == 0) {
+      mine[D] = m_run;
+      mine[D + 1] = l_run;
+    }
+  }
+  __syncthreads();
+  const int nq = min(16, a.group - 16 * qb);
+  for (int idx = tid; idx < nq * RED; idx += 256) {
+    const int qi = idx / RED, e = idx % RED;
+    float mw[4], m = -INFINITY;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+      mw[ww] = red[(ww * 16 + qi) * RED + D];
+      m = fmaxf(m, mw[ww]);
+    }
+    float val;
+    if (e == D) {
+      val = m;
+    } else {
+      val = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < 4; ++ww) {
+        const float wgt = fast_exp2((mw[ww] - m) * a.scale_log2);   // exp2(-inf) = 0 for idle waves
+        val += wgt * red[(ww * 16 + qi) * RED + e];                 // e == D+1 merges l the same way
+      }
+    }
+    const int head = kvh * a.group + 16 * qb + qi;
+    a.partials[(((int64_t)b * a.hq + head) * a.n_chunks + ci) * RED + e] = val;
+  }
+}
+
+// Merge the chunks of one (sequence, query head): out = sum_c w_c O_c / sum_c w_c l_c,
+// w_c = exp(m_c - max m), chunks taken in index order.
+struct CombineArgs {
+  const float* partials;
+  const int32_t* kv_len;
+  const uint8_t* mode;
+  int capacity, hq, n_sink, window, chunk, n_chunks, out_fp32;
+  float scale_log2;
+  void* out;
+};
+
+template <int D>
+__global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
+  constexpr int RED = D + 2;
+  const int d = threadIdx.x, head = blockIdx.x, b = blockIdx.y;
+  int len = a.kv_len[b];
+  len = len < 0 ? 0 : (len > a.capacity ? a.capacity : len);
+  bool sparse;
+  const int n_vis = visible_len(len, a.mode[b], a.n_sink, a.window, sparse);
+  const int nc = min((n_vis + a.chunk - 1) / a.chunk, a.n_chunks);   // chunks the launch covered
+  const float* base = a.partials + ((int64_t)b * a.hq + head) * a.n_chunks * RED;
+  float m = -INFINITY;
+  for (int c = 0; c < nc; ++c) m = fmaxf(m, base[c * RED + D]);
+  float num = 0.f, den = 0.f;
+  for (int c = 0; c < nc; ++c) {
+    const float wgt = fast_exp2((base[c * RED + D] - m) * a.scale_log2);
+    num += wgt * base[c * RED + d];
+    den += wgt * base[c * RED + D + 1];
+  }
+  const float r = nc > 0 ? num / den : 0.f;                 // an empty cache yields zeros
+  const int64_t off = ((int64_t)b * a.hq + head) * D + d;
+  if (a.out_fp32) ((float*)a.out)[off] = r;
+  else ((__bf16*)a.out)[off] = (__bf16)r;
+}
+
+DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len) {
+  // Aim for about 2048 workgroups (8 per CU) so the tail is short, with chunks of at least 256
+  // keys (64 per wave) so the per-chunk merge stays a small fraction of the streaming.
+  const long long pairs = (long long)batch * cfg.n_kv_heads;
+  long long total = pairs * (long long)(max_kv_len > 0 ? max_kv_len : 1);
+  long long chunk = (total + 2047) / 2048;
+  chunk = ((chunk + 127) / 128) * 128;
+  if (chunk < 256) chunk = 256;
+  DecodePlan p;
+  p.chunk = (int)chunk;
+  p.n_chunks = (int)(((long long)(max_kv_len > 0 ? max_kv_len : 1) + chunk - 1) / chunk);
+  return p;
+}
+
+size_t decode_partials_bytes(const flux_attn_cfg& cfg, int batch, const DecodePlan& p) {
+  return (size_t)batch * cfg.n_q_heads * p.n_chunks * (cfg.head_dim + 2) * sizeof(float);
+}
+
+hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
+                         const flux_kv_cache& cache, const uint8_t* mode, void* out, hipStream_t s) {
+  const DecodePlan plan = plan_decode(cfg, cache.batch, max_kv_len);
+  const float scale = cfg.softmax_scale != 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.head_dim);
+  DecodeArgs a;
+  a.q = (const __bf16*)q;
+  a.k = (const __bf16*)cache.k;
+  a.v = (const __bf16*)cache.v;
+  a.stride_b = cache.stride_b;
+  a.stride_h = cache.stride_h;
+  a.stride_t = cache.stride_t;
+  a.kv_len = cache.kv_len;
+  a.mode = mode;
+  a.capacity = cache.capacity;
+  a.hq = cfg.n_q_heads;
+  a.hkv = cfg.n_kv_heads;
+  a.group = cfg.n_q_heads / cfg.n_kv_heads;
+  a.qblocks = (a.group + 15) / 16;
+  a.n_sink = cfg.n_sink;
+  a.window = cfg.window;
+  a.chunk = plan.chunk;
+  a.n_chunks = plan.n_chunks;
+  a.scale_log2 = scale * kLog2e;
+  a.partials = c.partials;
+  const dim3 grid(plan.n_chunks, cfg.n_kv_heads * a.qblocks, cache.batch);
+  if (cfg.head_dim == 128) hipLaunchKernelGGL(decode_splitk_kernel<128>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(decode_splitk_kernel<64>, grid, dim3(256), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  CombineArgs ca;
+  ca.partials = c.partials;
+  ca.kv_len = cache.kv_len;
+  ca.mode = mode;
+  ca.capacity = cache.capacity;
+  ca.hq = cfg.n_q_heads;
+  ca.n_sink = cfg.n_sink;
+  ca.window = cfg.window;
+  ca.chunk = plan.chunk;
+  ca.n_chunks = plan.n_chunks;
+  ca.out_fp32 = cfg.out_dtype;
+  ca.scale_log2 = a.scale_log2;
+  ca.out = out;
+  const dim3 cgrid(cfg.n_q_heads, cache.batch);
+  if (cfg.head_dim == 128) hipLaunchKernelGGL(decode_combine_kernel<128>, cgrid, dim3(128), 0, s, ca);
+  else hipLaunchKernelGGL(decode_combine_kernel<64>, cgrid, dim3(64), 0, s, ca);
+  return hipGetLastError();
+}
+
+}  // namespace flux

@@ -1,0 +1,91 @@
+// Internal declarations shared by the translation units of libflux (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/flux.h"
+
+namespace flux {
+
+// ---- vector types for MFMA operands and packed memory access --------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+
+#define FLUX_LDS __attribute__((address_space(3)))
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// The context: a device workspace carved into fixed regions.
+struct Ctx {
+  int device;              // < 0: no device (argument checking only)
+  char* ws;                // device workspace base (256-byte aligned)
+  size_t ws_bytes;
+  // carved regions (device pointers)
+  uint32_t* status;        // sticky status word
+  uint32_t* counters;      // kCounters zero-initialised arrival counters; users reset them to zero
+  float* small;            // router scratch: pooled vectors and hidden activations
+  float* partials;         // split-K partial results
+  size_t partials_bytes;
+};
+
+constexpr int kCounters = 64;
+constexpr size_t kSmallBytes = 8u << 20;      // router: batch * (splits * hidden + inner) floats
+constexpr size_t kHeaderBytes = 4096;         // status + counters
+
+// ---- launchers (each validates nothing: flux_api.hip has done it) ---------------------------
+hipError_t launch_kv_append(const Ctx& c, const flux_kv_cache& cache, int hkv, int d, const void* k_new,
+                            const void* v_new, const int32_t* cu_new, int total_new, hipStream_t s);
+
+struct DecodePlan {
+  int chunk;        // keys per workgroup
+  int n_chunks;     // grid.x
+};
+DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len);
+size_t decode_partials_bytes(const flux_attn_cfg& cfg, int batch, const DecodePlan& p);
+hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
+                         const flux_kv_cache& cache, const uint8_t* mode, void* out, hipStream_t s);
+
+hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q, const int32_t* cu_q,
+                          int max_q_len, int max_kv_len, const flux_kv_cache& cache, const uint8_t* mode,
+                          void* out, hipStream_t s);
+
+hipError_t launch_router(const Ctx& c, const void* x, const int32_t* cu_seqlens, int batch, int hidden, int pool,
+                         const void* w1, const void* b1, const void* w2, const void* b2, int inner,
+                         uint8_t* mode_out, float* logits_out, hipStream_t s);
+
+// ---- small device helpers -------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+  return __builtin_bit_cast(float, bits16 << 16);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __builtin_bit_cast(float, packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __builtin_bit_cast(float, packed & 0xFFFF0000u); }
+
+// two fp32 -> packed bf16 pair (round to nearest even), low half = a
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  bf16x2 r;
+  r[0] = (__bf16)a;
+  r[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// max over the two half-waves: lane l and lane l^32 end up with the same value
+__device__ __forceinline__ float max_across_halves(float x) {
+  uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float x) {
+  uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+
+}  // namespace flux

@@ -1,0 +1,188 @@
+// flux_router: Layer Router in its inference form (Sec. 3.1): prefix/suffix pooling of the first
+// and last `pool` token rows (App. C.1) -> Context Encoder Linear+SiLU -> Router Head Linear ->
+// argmax (tie to FA).  Everything after the bf16 loads is fp32; nothing is rounded in between.
+//
+// Two launches, both tiny and latency-bound:
+//  1. router_pool: partial column sums of the pooled rows.  grid (column blocks, row splits, batch);
+//     a lane owns 8 adjacent columns (one 16-byte load per row), the 4 waves of a workgroup take
+//     different rows and are merged in LDS.  Row splits keep whole-sequence pooling (pool = 0) spread
+//     over the chip; with pool > 0 the cost is independent of the sequence length.
+//  2. router_mlp: grid (inner/8, batch); each wave produces two hidden units (dot of a bf16 W1 row
+//     with the pooled fp32 vector held in LDS).  The workgroup that arrives last (arrival counter)
+//     evaluates the two logits of every sequence in a fixed order and writes the decisions.
+#include "flux_internal.h"
+
+namespace flux {
+
+struct PoolArgs {
+  const __bf16* x;
+  const int32_t* cu;
+  int hidden, pool, splits;
+  float* psum;            // [batch, splits, hidden]
+};
+
+// pooled row number t (0-based among the pooled rows) -> row of the sequence
+__device__ __forceinline__ int pooled_row(int t, int n_rows, int pool, bool all) {
+  return (all || t < pool) ? t : n_rows - 2 * pool + t;
+}
+
+__global__ __launch_bounds__(256) void router_pool_kernel(PoolArgs a) {
+  __shared__ float red[4][512];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+  const int col = blockIdx.x * 512 + l * 8;
+  const int split = blockIdx.y, b = blockIdx.z;
+  const int r0 = a.cu[b];
+  const int n_rows = a.cu[b + 1] - r0;
+  const bool all = a.pool <= 0 || n_rows <= 2 * a.pool;
+  const int n_pooled = all ? n_rows : 2 * a.pool;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (col < a.hidden) {
+    for (int t = split * 4 + w; t < n_pooled; t += 4 * a.splits) {
+      const int row = r0 + pooled_row(t, n_rows, a.pool, all);
+      const u32x4 v = *(const u32x4*)(a.x + (int64_t)row * a.hidden + col);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += bf16_lo(v[i]);
+        acc[2 * i + 1] += bf16_hi(v[i]);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) red[w][l * 8 + i] = acc[i];
+  __syncthreads();
+  for (int c = tid; c < 512; c += 256) {
+    const int cc = blockIdx.x * 512 + c;
+    if (cc < a.hidden)
+      a.psum[((int64_t)b * a.splits + split) * a.hidden + cc] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+  }
+}
+
+struct MlpArgs {
+  const float* psum;      // [batch, splits, hidden]
+  const int32_t* cu;
+  const __bf16* w1;
+  const __bf16* b1;
+  const __bf16* w2;
+  const __bf16* b2;
+  float* hbuf;            // [batch, inner]
+  int batch, hidden, inner, pool, splits;
+  uint32_t* counter;
+  uint8_t* mode_out;
+  float* logits_out;
+};
+
+__global__ __launch_bounds__(256) void router_mlp_kernel(MlpArgs a) {
+  extern __shared__ float pvec[];                           // hidden floats
+  __shared__ int is_last;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+  const int b = blockIdx.y;
+  const int n_rows = a.cu[b + 1] - a.cu[b];
+  const bool all = a.pool <= 0 || n_rows <= 2 * a.pool;
+  const int n_pooled = all ? n_rows : 2 * a.pool;
+  const float inv = n_pooled > 0 ? 1.0f / (float)n_pooled : 0.f;
+  for (int c = tid; c < a.hidden; c += 256) {
+    float s = 0.f;
+    for (int sp = 0; sp < a.splits; ++sp) s += a.psum[((int64_t)b * a.splits + sp) * a.hidden + c];
+    pvec[c] = s * inv;
+  }
+  __syncthreads();
+  // two hidden units per wave
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int j = blockIdx.x * 8 + w * 2 + u;
+    if (j < a.inner) {
+      const __bf16* wrow = a.w1 + (int64_t)j * a.hidden;
+      float acc = 0.f;
+      for (int c = l * 8; c < a.hidden; c += 512) {
+        const u32x4 v = *(const u32x4*)(wrow + c);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc = __builtin_fmaf(bf16_lo(v[i]), pvec[c + 2 * i], acc);
+          acc = __builtin_fmaf(bf16_hi(v[i]), pvec[c + 2 * i + 1], acc);
+        }
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+      if (l == 0) {
+        if (a.b1) acc += (float)a.b1[j];
+        a.hbuf[(int64_t)b * a.inner + j] = acc / (1.0f + expf(-acc));   // SiLU
+      }
+    }
+  }
+  // ---- the last workgroup to arrive turns every sequence's hidden vector into logits
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const uint32_t prev = atomicAdd(a.counter, 1u);
+    is_last = (prev == gridDim.x * gridDim.y - 1);
+  }
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();
+  for (int bb = w; bb < a.batch; bb += 4) {
+    float s0 = 0.f, s1 = 0.f;
+    for (int j = l; j < a.inner; j += 64) {
+      const float hv = a.hbuf[(int64_t)bb * a.inner + j];
+      s0 = __builtin_fmaf((float)a.w2[j], hv, s0);
+      s1 = __builtin_fmaf((float)a.w2[a.inner + j], hv, s1);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      s0 += __shfl_xor(s0, off);
+      s1 += __shfl_xor(s1, off);
+    }
+    if (l == 0) {
+      if (a.b2) {
+        s0 += (float)a.b2[0];
+        s1 += (float)a.b2[1];
+      }
+      a.mode_out[bb] = s0 >= s1 ? 1 : 0;                     // argmax, tie -> index 0 = FA
+      if (a.logits_out) {
+        a.logits_out[2 * bb] = s0;
+        a.logits_out[2 * bb + 1] = s1;
+      }
+    }
+  }
+  if (tid == 0) *a.counter = 0;
+}
+
+hipError_t launch_router(const Ctx& c, const void* x, const int32_t* cu_seqlens, int batch, int hidden, int pool,
+                         const void* w1, const void* b1, const void* w2, const void* b2, int inner,
+                         uint8_t* mode_out, float* logits_out, hipStream_t s) {
+  // row splits: ~32 pooled rows per workgroup when the count is known, 32 splits for whole-sequence
+  // pooling, bounded by the scratch region
+  int splits = pool > 0 ? (2 * pool + 31) / 32 : 32;
+  const size_t per_split = (size_t)batch * hidden * sizeof(float);
+  const size_t hbytes = (size_t)batch * inner * sizeof(float);
+  size_t room = kSmallBytes - hbytes;
+  if ((size_t)splits * per_split > room) splits = (int)(room / per_split);
+  if (splits < 1) return hipErrorInvalidValue;              // flux_router has checked the sizes
+  float* psum = c.small;
+  float* hbuf = c.small + (size_t)splits * batch * hidden;
+
+  PoolArgs pa{(const __bf16*)x, cu_seqlens, hidden, pool, splits, psum};
+  hipLaunchKernelGGL(router_pool_kernel, dim3((hidden + 511) / 512, splits, batch), dim3(256), 0, s, pa);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  MlpArgs ma;
+  ma.psum = psum;
+  ma.cu = cu_seqlens;
+  ma.w1 = (const __bf16*)w1;
+  ma.b1 = (const __bf16*)b1;
+  ma.w2 = (const __bf16*)w2;
+  ma.b2 = (const __bf16*)b2;
+  ma.hbuf = hbuf;
+  ma.batch = batch;
+  ma.hidden = hidden;
+  ma.inner = inner;
+  ma.pool = pool;
+  ma.splits = splits;
+  ma.counter = c.counters + 1;
+  ma.mode_out = mode_out;
+  ma.logits_out = logits_out;
+  hipLaunchKernelGGL(router_mlp_kernel, dim3((inner + 7) / 8, batch), dim3(256), hidden * sizeof(float), s, ma);
+  return hipGetLastError();
+}
+
+}  // namespace flux

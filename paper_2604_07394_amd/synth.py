@@ -11,12 +11,15 @@ The same generator exists twice, bit for bit:
 * in ``csrc/synth_fill.hip`` (device side, fills large tensors in place).
 
 To make the two agree bit-exactly the transform from hash bits to a Gaussian
-uses only operations that IEEE-754 fixes completely: integer arithmetic,
-int->float conversion of values below 2**24, and single fp32 ``+ - * /`` and
-``sqrt`` roundings in a fixed order (no fused multiply-add, no library
-``log``/``cos``).  ``ln`` is evaluated with the atanh series on a reduced
-mantissa and ``cos`` with a Taylor polynomial on one quadrant; both are
-accurate to about 1e-7, far below the bf16 rounding applied afterwards.
+uses only operations that IEEE-754 fixes completely and that every
+implementation rounds alike: integer arithmetic, int->float conversion of
+values below 2**24, and single fp32 ``+ - *`` roundings in a fixed order (no
+fused multiply-add, no division, no ``sqrt``, no library ``log``/``cos``: a GPU
+may round those differently in the last bit).  ``ln`` is evaluated with the
+atanh series on a reduced mantissa, its reciprocal and the square root with
+Newton iterations from fixed starting values, and ``cos`` with a Taylor
+polynomial on one quadrant; all are accurate to a few 1e-7, far below the bf16
+rounding applied afterwards.
 
 Distribution: ``hash -> (u1, u2)`` two 24-bit uniforms, Box-Muller
 ``z = sqrt(-2 ln u1) * cos(2 pi u2)`` (one normal per counter).
@@ -76,6 +79,28 @@ def _horner(coeffs, x):
     return acc
 
 
+def _recip_1p7_2p5(d):
+    """1/d for d in (1.7, 2.5) by Newton's iteration on d/4 (multiplies and adds only)."""
+    dq = d * f32(0.25)
+    y = f32(48.0 / 17.0) - f32(32.0 / 17.0) * dq
+    for _ in range(4):
+        e = f32(1.0) - dq * y
+        y = y + y * e
+    return y * f32(0.25)
+
+
+def _sqrt_newton(x):
+    """sqrt(x) for x >= 0 as x * rsqrt(x): bit-level first guess, four Newton steps on rsqrt."""
+    xb = np.ascontiguousarray(x, dtype=f32).view(np.uint32)
+    y = (np.uint32(0x5F3759DF) - (xb >> np.uint32(1))).view(f32)
+    for _ in range(4):
+        t = x * y
+        t = t * y
+        t = f32(1.5) - f32(0.5) * t
+        y = y * t
+    return x * y
+
+
 def uniform_f32(seed: int, stream: int, counter, lo: float = 0.0, hi: float = 1.0) -> np.ndarray:
     """``lo + (hi-lo) * k/2**24`` with ``k`` the top 24 hash bits (fp32, two roundings)."""
     h = hash_u64(seed, stream, counter)
@@ -98,12 +123,12 @@ def normal_f32(seed: int, stream: int, counter) -> np.ndarray:
     big = m > _SQRT2
     m = np.where(big, m * f32(0.5), m)                  # (sqrt(.5), sqrt(2)]
     e = e + big.astype(np.int32)
-    s = (m - f32(1.0)) / (m + f32(1.0))
+    s = (m - f32(1.0)) * _recip_1p7_2p5(m + f32(1.0))
     s2 = s * s
     ln_m = s * _horner(_LN_C, s2)
     neg_ln = (np.int32(24) - e).astype(f32) * _LN2 - ln_m
     neg_ln = np.maximum(neg_ln, f32(0.0))
-    r = np.sqrt(neg_ln + neg_ln)
+    r = _sqrt_newton(neg_ln + neg_ln)
 
     # ---- cos(2 pi u2), u2 = k2 / 2**24: quadrant from the top two bits
     quad = k2 >> np.uint32(22)

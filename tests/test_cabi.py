@@ -1,0 +1,121 @@
+"""The C ABI without a GPU: the library loads, exports every symbol include/flux.h declares, and
+rejects bad arguments on the host before anything could be launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def F():
+    lib = os.path.join(ROOT, "paper_2604_07394_amd", "lib", "libflux.so")
+    if not os.path.exists(lib):
+        from paper_2604_07394_amd import build
+        build.build_all()
+    from paper_2604_07394_amd import binding
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flux.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(flux_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(F):
+    names = declared_symbols()
+    assert set(names) == set(F.EXPORTS)
+    lib = C.CDLL(F.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror_texts(F):
+    assert F.flux_strerror(0) == "ok"
+    assert "invalid" in F.flux_strerror(F.FLUX_EINVAL)
+    assert "capacity" in F.flux_strerror(F.FLUX_ECAPACITY)
+    assert "workspace" in F.flux_strerror(F.FLUX_EWORKSPACE)
+
+
+def test_workspace_needed_is_host_arithmetic(F):
+    cfg = F.attn_cfg(32, 8, 128, 128, 4096)
+    small = F.flux_workspace_needed(cfg, 1, 4096)
+    big = F.flux_workspace_needed(cfg, 8, 131072 + 128)
+    assert 0 < small < big < (1 << 30)
+    assert F.flux_workspace_needed(F.attn_cfg(32, 5, 128, 0, 1), 1, 100) == 0       # bad head ratio
+    assert F.flux_workspace_needed(cfg, 0, 100) == 0
+
+
+@pytest.fixture()
+def nodev(F):
+    ctx = F.flux_create(-1, 0)          # a context without a device: validation only
+    yield ctx
+    F.flux_destroy(ctx)
+
+
+def cache_struct(F, **kw):
+    d = dict(k=4096, v=8192, stride_b=128 * 64 * 2, stride_h=128 * 64, stride_t=128, kv_len=256, batch=1, capacity=64)
+    d.update(kw)
+    return F.FluxKVCache(d["k"], d["v"], d["stride_b"], d["stride_h"], d["stride_t"], d["kv_len"], d["batch"], d["capacity"])
+
+
+def rc_of(F, fn, *a):
+    try:
+        fn(*a)
+    except F.FluxError as e:
+        return e.code
+    return 0
+
+
+def test_attention_argument_validation(F, nodev):
+    good = F.attn_cfg(8, 2, 128, 4, 16)
+    kc = cache_struct(F)
+    args = lambda cfg=good, cache=kc, q=4096, mq=8, mk=32, mode=512, out=1024: (nodev, cfg, q, 768, mq, mk, cache, mode, out)
+    # a fully valid call gets past validation and then reports the missing device
+    assert rc_of(F, F.flux_attn_prefill, *args()) == F.FLUX_EHIP
+    assert rc_of(F, F.flux_attn_prefill, *args(cfg=F.attn_cfg(8, 3, 128, 4, 16))) == F.FLUX_EINVAL      # Hq % Hkv
+    assert rc_of(F, F.flux_attn_prefill, *args(cfg=F.attn_cfg(8, 2, 96, 4, 16))) == F.FLUX_EINVAL       # head_dim
+    assert rc_of(F, F.flux_attn_prefill, *args(cfg=F.attn_cfg(8, 2, 128, -1, 16))) == F.FLUX_EINVAL     # sinks
+    assert rc_of(F, F.flux_attn_prefill, *args(cfg=F.attn_cfg(8, 2, 128, 4, 0))) == F.FLUX_EINVAL       # window
+    assert rc_of(F, F.flux_attn_prefill, *args(cfg=F.attn_cfg(8, 2, 128, 4, 16, out_dtype=3))) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_attn_prefill, *args(q=None)) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_attn_prefill, *args(q=4100)) == F.FLUX_EINVAL                                # alignment
+    assert rc_of(F, F.flux_attn_prefill, *args(mode=None)) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_attn_prefill, *args(mq=40, mk=32)) == F.FLUX_EINVAL                          # more queries than keys
+    assert rc_of(F, F.flux_attn_prefill, *args(mk=65)) == F.FLUX_ECAPACITY
+    assert rc_of(F, F.flux_attn_prefill, *args(cache=cache_struct(F, stride_t=64))) == F.FLUX_EINVAL    # stride < D
+    assert rc_of(F, F.flux_attn_prefill, *args(cache=cache_struct(F, stride_t=132))) == F.FLUX_EINVAL   # 16-byte rule
+    assert rc_of(F, F.flux_attn_prefill, *args(cache=cache_struct(F, k=None))) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_attn_prefill, None, good, 4096, 768, 8, 32, kc, 512, 1024) == F.FLUX_EINVAL  # no context
+
+    dargs = lambda cfg=good, cache=kc, mk=32: (nodev, cfg, 4096, mk, cache, 512, 1024)
+    assert rc_of(F, F.flux_attn_decode, *dargs()) == F.FLUX_EHIP
+    assert rc_of(F, F.flux_attn_decode, *dargs(mk=-1)) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_attn_decode, *dargs(mk=100)) == F.FLUX_ECAPACITY
+    assert rc_of(F, F.flux_attn_decode, *dargs(cfg=F.attn_cfg(8, 0, 128, 4, 16))) == F.FLUX_EINVAL
+
+
+def test_append_and_router_argument_validation(F, nodev):
+    kc = cache_struct(F)
+    ok = (nodev, kc, 2, 128, 4096, 8192, 256, 10, 10)
+    assert rc_of(F, F.flux_kv_append, *ok) == F.FLUX_EHIP
+    assert rc_of(F, F.flux_kv_append, nodev, kc, 2, 128, 4096, 8192, 256, 100, 65) == F.FLUX_ECAPACITY
+    assert rc_of(F, F.flux_kv_append, nodev, kc, 2, 128, 4096, 8192, 256, 5, 6) == F.FLUX_EINVAL        # max_new > total
+    assert rc_of(F, F.flux_kv_append, nodev, kc, 2, 100, 4096, 8192, 256, 5, 5) == F.FLUX_EINVAL        # head_dim
+    assert rc_of(F, F.flux_kv_append, nodev, kc, 2, 128, None, 8192, 256, 5, 5) == F.FLUX_EINVAL
+
+    r_ok = (nodev, 4096, 256, 2, 4096, 100, 8192, None, 16384, None, 256, 512, None)
+    assert rc_of(F, F.flux_router, *r_ok) == F.FLUX_EHIP
+    bad_hidden = list(r_ok); bad_hidden[4] = 4100
+    assert rc_of(F, F.flux_router, *bad_hidden) == F.FLUX_EINVAL
+    bad_inner = list(r_ok); bad_inner[10] = 0
+    assert rc_of(F, F.flux_router, *bad_inner) == F.FLUX_EINVAL
+    bad_pool = list(r_ok); bad_pool[5] = -1
+    assert rc_of(F, F.flux_router, *bad_pool) == F.FLUX_EINVAL
+    no_out = list(r_ok); no_out[11] = None
+    assert rc_of(F, F.flux_router, *no_out) == F.FLUX_EINVAL
+    huge = list(r_ok); huge[3] = 4096
+    assert rc_of(F, F.flux_router, *huge) == F.FLUX_EWORKSPACE

@@ -1,0 +1,364 @@
+"""GPU parity: every entry point of libflux against the fp64 CPU oracle, element by element, on the
+same seeded inputs.  Tolerance for attention (bf16 inputs, fp32 accumulation, fp32 output):
+max-abs 1e-2 and relative L2 5e-3; router decisions are bit-exact outside a 1e-6 logit margin;
+copies and lengths are bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flux_oracle as O
+from paper_2604_07394_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+FA, SA = 1, 0
+
+
+@pytest.fixture(scope="module")
+def F():
+    from paper_2604_07394_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(F):
+    c = F.flux_create(0, 0)
+    yield c
+    F.flux_destroy(c)
+
+
+def i32(x):
+    return torch.tensor(x, dtype=torch.int32, device="cuda")
+
+
+def u8(x):
+    return torch.tensor(x, dtype=torch.uint8, device="cuda")
+
+
+def cu(lens):
+    return i32(np.concatenate([[0], np.cumsum(lens)]))
+
+
+class Layer:
+    """Drives one layer through the C ABI and mirrors it in the oracle."""
+
+    def __init__(self, F, ctx, seed, batch, hq, hkv, d, capacity, n_sink, window, layer=0, scales=False):
+        self.F, self.ctx, self.seed, self.layer = F, ctx, seed, layer
+        self.B, self.hq, self.hkv, self.d = batch, hq, hkv, d
+        self.cfg = F.attn_cfg(hq, hkv, d, n_sink, window, 0.0, 1)
+        self.n_sink, self.window = n_sink, window
+        self.cache = F.KVCache.empty(batch, hkv, capacity, d)
+        self.ocache = O.KVCache(batch, hkv, d)
+        self.lens = [0] * batch
+        self.counter = 0
+        self.qs = self.ks = self.vs = None
+        if scales:
+            self.qs = synth.head_scales(seed, synth.stream_id(synth.STREAM_QSCALE, layer), hq)
+            self.ks = synth.head_scales(seed, synth.stream_id(synth.STREAM_KSCALE, layer), hkv)
+            self.vs = synth.head_scales(seed, synth.stream_id(synth.STREAM_VSCALE, layer), hkv)
+
+    def _draw(self, kind, rows, heads, scale):
+        bits = synth.normal_bf16(self.seed, synth.stream_id(kind, self.layer), (rows, heads, self.d),
+                                 scale, 1 if scale is not None else None, counter0=self.counter)
+        self.counter += rows * heads * self.d
+        return bits
+
+    def new_tokens(self, n_new):
+        """Draw q/k/v for n_new[b] new tokens per sequence (packed), as bit patterns."""
+        t = int(sum(n_new))
+        return (self._draw(synth.STREAM_Q, t, self.hq, self.qs), self._draw(synth.STREAM_K, t, self.hkv, self.ks),
+                self._draw(synth.STREAM_V, t, self.hkv, self.vs))
+
+    def append(self, kb, vb, n_new):
+        F = self.F
+        F.flux_kv_append(self.ctx, self.cache, self.hkv, self.d, H.bits_to_torch(kb), H.bits_to_torch(vb),
+                         cu(n_new), int(sum(n_new)), int(max(n_new)))
+        off = 0
+        for b, n in enumerate(n_new):
+            self.ocache.append(b, O.bf16_to_f64(kb[off:off + n]), O.bf16_to_f64(vb[off:off + n]))
+            self.lens[b] += n
+            off += n
+
+    def prefill(self, qb, n_q, modes):
+        F = self.F
+        t = int(sum(n_q))
+        out = torch.full((t, self.hq, self.d), float("nan"), dtype=torch.float32, device="cuda")
+        F.flux_attn_prefill(self.ctx, self.cfg, H.bits_to_torch(qb), cu(n_q), int(max(n_q)), int(max(self.lens)),
+                            self.cache, u8(modes), out)
+        torch.cuda.synchronize()
+        ref = []
+        off = 0
+        for b, n in enumerate(n_q):
+            if n:
+                ref.append(O.attention(O.bf16_to_f64(qb[off:off + n]), self.ocache.k[b], self.ocache.v[b],
+                                       int(modes[b]), self.n_sink, self.window))
+            off += n
+        return out.cpu().numpy(), np.concatenate(ref, axis=0)
+
+    def decode(self, qb, modes, max_kv_len=None):
+        F = self.F
+        out = torch.full((self.B, self.hq, self.d), float("nan"), dtype=torch.float32, device="cuda")
+        F.flux_attn_decode(self.ctx, self.cfg, H.bits_to_torch(qb), int(max_kv_len or max(self.lens)), self.cache,
+                           u8(modes), out)
+        torch.cuda.synchronize()
+        qf = O.bf16_to_f64(qb)
+        ref = np.stack([O.attention(qf[b][None], self.ocache.k[b], self.ocache.v[b], int(modes[b]), self.n_sink,
+                                    self.window)[0] for b in range(self.B)])
+        return out.cpu().numpy(), ref
+
+
+# ----------------------------------------------------------------------------- generator
+
+def test_device_generator_matches_host_bits():
+    from paper_2604_07394_amd import synth_gpu
+    big = torch.zeros(3, 4, 40, 72, dtype=torch.bfloat16, device="cuda")
+    view = big[:, :, 3:36, :64]                        # strided view: capacity padding and wider rows
+    scale = synth.head_scales(5, synth.stream_id(synth.STREAM_KSCALE), 4)
+    synth_gpu.fill_normal_bf16(view, 5, synth.stream_id(synth.STREAM_K, 2), torch.from_numpy(scale).cuda(), 1,
+                               counter0=12345)
+    torch.cuda.synchronize()
+    host = synth.normal_bf16(5, synth.stream_id(synth.STREAM_K, 2), (3, 4, 33, 64), scale, 1, counter0=12345)
+    assert np.array_equal(H.torch_to_bits(view), host)
+    assert float(big[:, :, :3].abs().max()) == 0 and float(big[..., 64:].abs().max()) == 0
+    # a larger unscaled draw: 2M samples must agree bit for bit
+    t = torch.empty(1, 1, 8192, 256, dtype=torch.bfloat16, device="cuda")
+    synth_gpu.fill_normal_bf16(t, 9, 77)
+    assert np.array_equal(H.torch_to_bits(t), synth.normal_bf16(9, 77, (1, 1, 8192, 256)))
+
+
+# ----------------------------------------------------------------------------- kv append
+
+def test_kv_append_ragged_bit_exact(F, ctx):
+    lay = Layer(F, ctx, 11, 3, 4, 2, 64, 300, 4, 16)
+    for n_new in ([5, 0, 130], [1, 1, 1], [64, 7, 100]):
+        _, kb, vb = lay.new_tokens(n_new)
+        lay.append(kb, vb, n_new)
+    torch.cuda.synchronize()
+    assert lay.cache.kv_len.cpu().tolist() == lay.lens == [70, 8, 231]
+    for b in range(3):
+        k_dev = H.torch_to_f64(lay.cache.k[b, :, :lay.lens[b]]).transpose(1, 0, 2)
+        v_dev = H.torch_to_f64(lay.cache.v[b, :, :lay.lens[b]]).transpose(1, 0, 2)
+        assert np.array_equal(k_dev, lay.ocache.k[b]) and np.array_equal(v_dev, lay.ocache.v[b])
+    assert F.flux_last_device_status(ctx) == 0
+
+
+def test_kv_append_overflow_is_clamped_and_flagged(F, ctx):
+    lay = Layer(F, ctx, 12, 2, 2, 2, 64, 16, 0, 4)
+    _, kb, vb = lay.new_tokens([10, 3])
+    lay.append(kb, vb, [10, 3])
+    # 8 more rows for sequence 0 (only 6 fit), 0 for sequence 1
+    _, kb2, vb2 = lay.new_tokens([8, 0])
+    F.flux_kv_append(ctx, lay.cache, 2, 64, H.bits_to_torch(kb2), H.bits_to_torch(vb2), cu([8, 0]), 8, 8)
+    torch.cuda.synchronize()
+    assert lay.cache.kv_len.cpu().tolist() == [16, 3]
+    assert F.flux_last_device_status(ctx) & F.FLUX_DEV_KV_OVERFLOW
+    assert F.flux_last_device_status(ctx) == 0                      # sticky bit cleared by the read
+    got = H.torch_to_bits(lay.cache.k[0, :, 10:16]).transpose(1, 0, 2)
+    assert np.array_equal(got, kb2[:6])
+
+
+# ----------------------------------------------------------------------------- prefill
+
+def test_prefill_tiny_config_full_compare(F, ctx):
+    """The Tiny configuration: 4 layers [FA, SA, FA, SA], S 512, 8/2 heads, D 64, 16 sinks, window 128,
+    every output element compared; then 16 decode steps appending new rows."""
+    worst = (0.0, 0.0)
+    for layer, mode in enumerate([FA, SA, FA, SA]):
+        lay = Layer(F, ctx, 0, 1, 8, 2, 64, 512 + 16, 16, 128, layer=layer)
+        qb, kb, vb = lay.new_tokens([512])
+        lay.append(kb, vb, [512])
+        got, ref = lay.prefill(qb, [512], [mode])
+        e = H.assert_close(got, ref, f"tiny prefill layer {layer}")
+        worst = max(worst, e)
+        for step in range(16):
+            qb, kb, vb = lay.new_tokens([1])
+            lay.append(kb, vb, [1])
+            got, ref = lay.decode(qb.reshape(1, 8, 64), [mode])
+            H.assert_close(got, ref, f"tiny decode layer {layer} step {step}")
+    print("tiny worst (max-abs, rel-L2):", worst)
+
+
+@pytest.mark.parametrize("d,hq,hkv", [(128, 8, 2), (128, 7, 1), (64, 4, 4)])
+def test_prefill_ragged_multi_tile(F, ctx, d, hq, hkv):
+    """Ragged batch over several 128-row tiles with ragged tails, per-sequence modes, sinks and a
+    window that are not multiples of the 64-key block, per-head scales up to 2."""
+    lens = [700, 129, 64, 1]
+    modes = [SA, FA, SA, SA]
+    lay = Layer(F, ctx, 21, 4, hq, hkv, d, 704, 37, 150, scales=True)
+    qb, kb, vb = lay.new_tokens(lens)
+    lay.append(kb, vb, lens)
+    got, ref = lay.prefill(qb, lens, modes)
+    H.assert_close(got, ref, "ragged prefill")
+    # per-sequence check so that a short sequence cannot hide behind a long one
+    off = 0
+    for n in lens:
+        H.assert_close(got[off:off + n], ref[off:off + n], f"sequence of {n}")
+        off += n
+
+
+def test_prefill_chunked_equals_whole(F, ctx):
+    """Queries are the last n_q positions of the cache: a second chunk attends the first."""
+    lay = Layer(F, ctx, 22, 2, 4, 2, 128, 512, 8, 100)
+    q1, k1, v1 = lay.new_tokens([300, 200])
+    lay.append(k1, v1, [300, 200])
+    got1, ref1 = lay.prefill(q1, [300, 200], [SA, FA])
+    H.assert_close(got1, ref1, "first chunk")
+    q2, k2, v2 = lay.new_tokens([150, 0])
+    lay.append(k2, v2, [150, 0])
+    got2, ref2 = lay.prefill(q2, [150, 0], [SA, FA])
+    H.assert_close(got2, ref2, "second chunk")
+
+
+def test_prefill_sa_window_covering_everything_equals_fa(F, ctx):
+    lay = Layer(F, ctx, 23, 1, 4, 1, 128, 400, 0, 4096)
+    qb, kb, vb = lay.new_tokens([400])
+    lay.append(kb, vb, [400])
+    got_sa, ref = lay.prefill(qb, [400], [SA])
+    got_fa, _ = lay.prefill(qb, [400], [FA])
+    assert np.array_equal(got_sa, got_fa)
+    H.assert_close(got_sa, ref, "wide window")
+
+
+def test_prefill_bf16_output(F, ctx):
+    lay = Layer(F, ctx, 24, 1, 4, 2, 128, 256, 4, 64)
+    qb, kb, vb = lay.new_tokens([256])
+    lay.append(kb, vb, [256])
+    got32, ref = lay.prefill(qb, [256], [SA])
+    cfg16 = F.attn_cfg(4, 2, 128, 4, 64, 0.0, 0)
+    out16 = torch.empty(256, 4, 128, dtype=torch.bfloat16, device="cuda")
+    F.flux_attn_prefill(ctx, cfg16, H.bits_to_torch(qb), cu([256]), 256, 256, lay.cache, u8([SA]), out16)
+    torch.cuda.synchronize()
+    # the bf16 output is the fp32 output rounded once
+    assert torch.equal(out16.cpu(), torch.from_numpy(got32).to(torch.bfloat16))
+    got16 = H.torch_to_f64(out16)
+    assert (np.abs(got16 - ref) <= np.maximum(1e-2, 2.0 ** -8 * np.abs(ref))).all()
+
+
+def test_prefill_is_deterministic(F, ctx):
+    lay = Layer(F, ctx, 25, 2, 8, 2, 128, 384, 16, 128)
+    qb, kb, vb = lay.new_tokens([384, 200])
+    lay.append(kb, vb, [384, 200])
+    a, _ = lay.prefill(qb, [384, 200], [FA, SA])
+    b, _ = lay.prefill(qb, [384, 200], [FA, SA])
+    assert np.array_equal(a, b)
+
+
+# ----------------------------------------------------------------------------- decode
+
+@pytest.mark.parametrize("d,hq,hkv", [(128, 8, 2), (128, 7, 1), (64, 8, 2), (128, 40, 2)])
+def test_decode_ragged_multi_chunk(F, ctx, d, hq, hkv):
+    """Caches long enough for several split-K chunks, ragged lengths (one shorter than sinks+window,
+    one a single token), mixed modes, and group sizes 4, 7 and 20 (more than one MFMA column block)."""
+    lens = [3000, 1537, 100, 1]
+    modes = [FA, SA, SA, FA]
+    lay = Layer(F, ctx, 31, 4, hq, hkv, d, 3100, 24, 333, scales=True)
+    _, kb, vb = lay.new_tokens(lens)
+    lay.append(kb, vb, lens)
+    for step in range(3):
+        qb, kb, vb = lay.new_tokens([1, 1, 1, 1])
+        lay.append(kb, vb, [1, 1, 1, 1])
+        got, ref = lay.decode(qb.reshape(4, hq, d), modes)
+        for b in range(4):
+            H.assert_close(got[b], ref[b], f"decode step {step} seq {b} (len {lay.lens[b]})")
+
+
+def test_decode_equals_last_prefill_row_on_gpu(F, ctx):
+    lay = Layer(F, ctx, 32, 2, 8, 2, 128, 600, 16, 128)
+    qb, kb, vb = lay.new_tokens([600, 333])
+    lay.append(kb, vb, [600, 333])
+    pre, _ = lay.prefill(qb, [600, 333], [SA, FA])
+    q_last = np.stack([qb[599], qb[600 + 332]])
+    dec, ref = lay.decode(q_last, [SA, FA])
+    H.assert_close(dec, ref, "decode")
+    assert np.abs(dec[0] - pre[599]).max() < 2e-3 and np.abs(dec[1] - pre[600 + 332]).max() < 2e-3
+
+
+def test_decode_sparse_launch_sizing_and_never_reads_the_middle(F, ctx):
+    """An SA layer sized for n_sink + window keys gives the same result, and poisoning the hidden
+    middle of the cache with NaN does not change it: those rows are never read."""
+    lay = Layer(F, ctx, 33, 2, 8, 2, 128, 2100, 32, 256)
+    _, kb, vb = lay.new_tokens([2048, 1500])
+    lay.append(kb, vb, [2048, 1500])
+    qb, kb, vb = lay.new_tokens([1, 1])
+    lay.append(kb, vb, [1, 1])
+    q = qb.reshape(2, 8, 128)
+    full, ref = lay.decode(q, [SA, SA])
+    H.assert_close(full, ref, "sa decode")
+    small, _ = lay.decode(q, [SA, SA], max_kv_len=32 + 256)
+    assert np.array_equal(full, small)
+    lay.cache.k[0, :, 32:2049 - 256] = float("nan")
+    lay.cache.v[0, :, 32:2049 - 256] = float("nan")
+    lay.cache.k[1, :, 32:1501 - 256] = float("nan")
+    lay.cache.v[1, :, 32:1501 - 256] = float("nan")
+    poisoned, _ = lay.decode(q, [SA, SA])
+    assert np.array_equal(full, poisoned)
+
+
+def test_decode_is_deterministic(F, ctx):
+    lay = Layer(F, ctx, 34, 3, 8, 2, 128, 5000, 16, 512)
+    _, kb, vb = lay.new_tokens([5000, 2500, 700])
+    lay.append(kb, vb, [5000, 2500, 700])
+    qb, _, _ = lay.new_tokens([1, 1, 1])
+    a, _ = lay.decode(qb.reshape(3, 8, 128), [FA, SA, FA])
+    b, _ = lay.decode(qb.reshape(3, 8, 128), [FA, SA, FA])
+    assert np.array_equal(a, b)
+
+
+# ----------------------------------------------------------------------------- router
+
+def router_case(F, ctx, seed, lens, hidden, inner, pool, bias):
+    t = int(sum(lens))
+    xb = synth.normal_bf16(seed, synth.stream_id(synth.STREAM_X), (t, hidden))
+    w1f = synth.normal_f32(seed, synth.stream_id(synth.STREAM_W1), np.arange(inner * hidden, dtype=np.uint64)) * np.float32(0.02)
+    w2f = synth.normal_f32(seed, synth.stream_id(synth.STREAM_W2), np.arange(2 * inner, dtype=np.uint64)) * np.float32(0.02)
+    w1b = synth.f32_to_bf16_bits(w1f).reshape(inner, hidden)
+    w2b = synth.f32_to_bf16_bits(w2f).reshape(2, inner)
+    b1b = b2b = None
+    if bias:
+        b1b = synth.f32_to_bf16_bits(synth.normal_f32(seed, synth.stream_id(synth.STREAM_B1), np.arange(inner, dtype=np.uint64)) * np.float32(0.1))
+        b2b = synth.f32_to_bf16_bits(synth.normal_f32(seed, synth.stream_id(synth.STREAM_B2), np.arange(2, dtype=np.uint64)) * np.float32(0.01))
+    mode = torch.full((len(lens),), 7, dtype=torch.uint8, device="cuda")
+    logits = torch.full((len(lens), 2), float("nan"), dtype=torch.float32, device="cuda")
+    F.flux_router(ctx, H.bits_to_torch(xb), cu(lens), len(lens), hidden, pool, H.bits_to_torch(w1b),
+                  H.bits_to_torch(b1b) if bias else None, H.bits_to_torch(w2b), H.bits_to_torch(b2b) if bias else None,
+                  inner, mode, logits)
+    torch.cuda.synchronize()
+    x = O.bf16_to_f64(xb)
+    w1, w2 = O.bf16_to_f64(w1b), O.bf16_to_f64(w2b)
+    b1 = O.bf16_to_f64(b1b) if bias else None
+    b2 = O.bf16_to_f64(b2b) if bias else None
+    off = 0
+    margins = []
+    for b, n in enumerate(lens):
+        ref_logits, ref_mode = O.router(x[off:off + n], pool, w1, b1, w2, b2)
+        off += n
+        got = logits[b].cpu().numpy().astype(np.float64)
+        assert np.abs(got - ref_logits).max() < 1e-6, (b, got, ref_logits)
+        margin = abs(ref_logits[0] - ref_logits[1])
+        margins.append(margin)
+        if margin >= 1e-6:                                   # the stated tie margin
+            assert int(mode[b]) == ref_mode, (b, got, ref_logits)
+    return margins
+
+
+@pytest.mark.parametrize("pool", [100, 0, 3])
+@pytest.mark.parametrize("bias", [False, True])
+def test_router_matches_oracle(F, ctx, pool, bias):
+    margins = router_case(F, ctx, 4, [1000, 150, 200, 201, 1, 7], 4096, 256, pool, bias)
+    assert max(margins) >= 1e-6                              # the seed exercises real decisions
+
+
+def test_router_small_shapes(F, ctx):
+    router_case(F, ctx, 41, [5, 300], 64, 8, 2, True)
+    router_case(F, ctx, 42, [9], 1000, 24, 4, False)
+
+
+def test_router_zero_head_is_a_tie_and_goes_to_fa(F, ctx):
+    x = torch.randn(50, 256, device="cuda").to(torch.bfloat16)
+    w1 = (torch.randn(16, 256, device="cuda") * 0.02).to(torch.bfloat16)
+    w2 = torch.zeros(2, 16, dtype=torch.bfloat16, device="cuda")
+    mode = torch.full((1,), 7, dtype=torch.uint8, device="cuda")
+    F.flux_router(ctx, x, cu([50]), 1, 256, 10, w1, None, w2, None, 16, mode)
+    torch.cuda.synchronize()
+    assert int(mode[0]) == FA

@@ -1,0 +1,313 @@
+#!/usr/bin/env python3
+"""Benchmark of the Flux Attention hot path on one MI355X.
+
+A timed "step" is one prefill pass of the whole attention stack of the stack-prefill workload
+(32 layers x [flux_kv_append + flux_attn_prefill], batch 1, 32768 tokens, 32/8 heads, D 128,
+16 of 32 layers SA with 128 sinks + 4096 window), inputs resident in HBM.  `value` is prefill
+tokens/s of that routed mix.  The same run also times the all-FA mask (speedup of the mix), the
+long-context decode workload (32 layers, batch 8, 131072 cached tokens; ms per step, mix and all-FA),
+the router, and the CPU oracle on a bounded sample (`cpu_baseline`).
+
+Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is single-GPU.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--decode-steps", type=int, default=50)
+    ap.add_argument("--decode-warmup", type=int, default=10)
+    ap.add_argument("--only", choices=["all", "prefill", "decode"], default="all",
+                    help="restrict the run (profiling); the JSON line then carries nulls for the rest")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--small", action="store_true", help="shrunken shapes for a quick functional check")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2604_07394_amd import binding as F
+    from paper_2604_07394_amd import synth, synth_gpu
+
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    ctx = F.flux_create(0, 0)
+
+    def i32(x):
+        return torch.tensor(x, dtype=torch.int32, device=dev)
+
+    result = {}
+
+    # ------------------------------------------------------------------ prefill: stack-prefill workload
+    L, S, HQ, HKV, D, NS, W, N_SA, SEED = 32, 32768, 32, 8, 128, 128, 4096, 16, 1
+    if args.small:
+        L, S, N_SA = 4, 4096, 2
+    G = HQ // HKV
+    mask_mix = synth.random_layer_mask(SEED, L, N_SA)            # 1 = FA, 0 = SA
+    cfg = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 0)                 # bf16 output, as the paper's BF16 runs
+
+    def pairs_fa(s):
+        return s * (s + 1) // 2
+
+    def pairs_sa(s):
+        return sum(min(i + 1, W) + max(0, min(NS, i + 1 - W)) for i in range(s))
+
+    flops_fa = 4.0 * D * HQ * pairs_fa(S)
+    flops_sa = 4.0 * D * HQ * pairs_sa(S)
+
+    prefill = None
+    roofline = None
+    cpu_baseline = None
+    if args.only in ("all", "prefill"):
+        q = torch.empty(L, S, HQ, D, dtype=torch.bfloat16, device=dev)
+        kn = torch.empty(L, S, HKV, D, dtype=torch.bfloat16, device=dev)
+        vn = torch.empty(L, S, HKV, D, dtype=torch.bfloat16, device=dev)
+        out = torch.empty(S, HQ, D, dtype=torch.bfloat16, device=dev)
+        caches = [F.KVCache.empty(1, HKV, S, D) for _ in range(L)]
+        for l in range(L):
+            qs = torch.from_numpy(synth.head_scales(SEED, synth.stream_id(synth.STREAM_QSCALE, l), HQ)).to(dev)
+            ks = torch.from_numpy(synth.head_scales(SEED, synth.stream_id(synth.STREAM_KSCALE, l), HKV)).to(dev)
+            vs = torch.from_numpy(synth.head_scales(SEED, synth.stream_id(synth.STREAM_VSCALE, l), HKV)).to(dev)
+            synth_gpu.fill_normal_bf16(q[l][None], SEED, synth.stream_id(synth.STREAM_Q, l), qs, 2)
+            synth_gpu.fill_normal_bf16(kn[l][None], SEED, synth.stream_id(synth.STREAM_K, l), ks, 2)
+            synth_gpu.fill_normal_bf16(vn[l][None], SEED, synth.stream_id(synth.STREAM_V, l), vs, 2)
+        cu = i32([0, S])
+        modes = {0: torch.zeros(1, dtype=torch.uint8, device=dev), 1: torch.ones(1, dtype=torch.uint8, device=dev)}
+        torch.cuda.synchronize()
+
+        def prefill_step(mask, events=None):
+            for l in range(L):
+                caches[l].kv_len.zero_()
+                F.flux_kv_append(ctx, caches[l], HKV, D, kn[l], vn[l], cu, S, S)
+                if events is not None:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                F.flux_attn_prefill(ctx, cfg, q[l], cu, S, S, caches[l], modes[int(mask[l])], out)
+                if events is not None:
+                    e1.record()
+                    events.append((int(mask[l]), e0, e1))
+
+        def time_steps(mask, steps, warmup, events=None):
+            for _ in range(warmup):
+                prefill_step(mask)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                prefill_step(mask, events)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps
+
+        ev = []
+        t_mix = time_steps(mask_mix, args.steps, args.warmup, ev)
+        fa_ms = [a.elapsed_time(b) for m, a, b in ev if m == 1]
+        sa_ms = [a.elapsed_time(b) for m, a, b in ev if m == 0]
+        t_fa = time_steps(np.ones(L, dtype=np.uint8), max(1, args.steps // 2), 1)
+        fa_avg = sum(fa_ms) / max(len(fa_ms), 1)
+        sa_avg = sum(sa_ms) / max(len(sa_ms), 1)
+        n_fa = int(mask_mix.sum())
+        pred = (L * flops_fa) / (n_fa * flops_fa + (L - n_fa) * flops_sa)
+        prefill = {
+            "tokens_per_s_mix": S / t_mix, "ms_per_step_mix": t_mix * 1e3,
+            "tokens_per_s_all_fa": S / t_fa, "ms_per_step_all_fa": t_fa * 1e3,
+            "speedup_mix_vs_all_fa": t_fa / t_mix, "predicted_speedup_from_flops": pred,
+            "omega_msr": float((mask_mix == 0).mean()),
+            "fa_kernel_ms": fa_avg, "sa_kernel_ms": sa_avg,
+            "sa_kernel_tflops": flops_sa / (sa_avg * 1e-3) / 1e12 if sa_ms else None,
+        }
+        achieved = flops_fa / (fa_avg * 1e-3) / 1e12
+        roofline = {"kernel": "prefill_kernel<128> (FA layers)", "bound": "mfma", "achieved": achieved,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                    "traffic": None, "flops_per_launch": flops_fa, "launch_ms": fa_avg}
+
+        # ---- CPU oracle on a bounded sample of the same workload (rank 0, N = 1)
+        if not args.no_cpu_baseline:
+            from oracle import flux_oracle as O
+            from tests import helpers as H
+            try:
+                from threadpoolctl import threadpool_info
+                cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+            except Exception:
+                cores = 1
+            rng = np.random.default_rng(0)
+            per_layer, n_rows = {}, {}
+            t_used = 0.0
+            budget = 1.0 if args.small else 9.0                 # seconds of oracle time per mode
+            for m in (1, 0):
+                layer = int(np.nonzero(mask_mix == m)[0][0])
+                kf = H.torch_to_f64(kn[layer][:, 0])             # KV head 0 of that layer, [S, D]
+                vf = H.torch_to_f64(vn[layer][:, 0])
+                qf = H.torch_to_f64(q[layer][:, :G])             # its G query heads, [S, G, D]
+                rows = rng.integers(0, S, size=100000)
+                t0 = time.perf_counter()
+                done = 0
+                while time.perf_counter() - t0 < budget and done < len(rows):
+                    i = int(rows[done])
+                    O.attention_row(qf[i], kf, vf, i, m, NS, W)
+                    done += 1
+                dt = time.perf_counter() - t0
+                t_used += dt
+                n_rows[m] = done
+                per_layer[m] = dt / done * S * HKV               # seconds for one whole layer
+            t_full = n_fa * per_layer[1] + (L - n_fa) * per_layer[0]
+            cpu_baseline = {"value": S / t_full, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                            "sample": "fp64 NumPy oracle (attention_row), %d FA + %d SA uniformly drawn query "
+                                      "positions of one KV group (%d heads) in one FA and one SA layer, %.1f s of CPU "
+                                      "work, extrapolated to %d layers x %d positions x %d groups"
+                                      % (n_rows[1], n_rows[0], G, t_used, L, S, HKV)}
+        del q, kn, vn, out, caches
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ decode: long-context decode workload
+    decode = None
+    if args.only in ("all", "decode"):
+        LD, B, N, SEED_D = 32, 8, 131072, 2
+        n_dec = args.decode_steps + args.decode_warmup
+        if args.small:
+            LD, B, N = 4, 2, 16384
+        cap = N + 2 * n_dec + 8
+        mask_d = synth.random_layer_mask(SEED_D, LD, LD // 2)
+        kc = torch.empty(LD, B, HKV, cap, D, dtype=torch.bfloat16, device=dev)
+        vc = torch.empty(LD, B, HKV, cap, D, dtype=torch.bfloat16, device=dev)
+        for l in range(LD):
+            synth_gpu.fill_normal_bf16(kc[l][:, :, :N], SEED_D, synth.stream_id(synth.STREAM_K, l))
+            synth_gpu.fill_normal_bf16(vc[l][:, :, :N], SEED_D, synth.stream_id(synth.STREAM_V, l))
+        kv_len = torch.full((LD, B), N, dtype=torch.int32, device=dev)
+        dcaches = [F.KVCache(kc[l], vc[l], kv_len[l]) for l in range(LD)]
+        qd = torch.empty(1, LD, B * HQ, D, dtype=torch.bfloat16, device=dev)
+        kd = torch.empty(1, LD, B * HKV, D, dtype=torch.bfloat16, device=dev)
+        vd = torch.empty(1, LD, B * HKV, D, dtype=torch.bfloat16, device=dev)
+        synth_gpu.fill_normal_bf16(qd, SEED_D, synth.stream_id(synth.STREAM_QDEC))
+        synth_gpu.fill_normal_bf16(kd, SEED_D, synth.stream_id(synth.STREAM_KDEC))
+        synth_gpu.fill_normal_bf16(vd, SEED_D, synth.stream_id(synth.STREAM_VDEC))
+        outd = torch.empty(B, HQ, D, dtype=torch.bfloat16, device=dev)
+        cu1 = i32(list(range(B + 1)))
+        dmodes = {0: torch.zeros(B, dtype=torch.uint8, device=dev), 1: torch.ones(B, dtype=torch.uint8, device=dev)}
+        torch.cuda.synchronize()
+        cur = {"n": N}
+
+        def decode_step(mask, events=None):
+            cur["n"] += 1
+            for l in range(LD):
+                F.flux_kv_append(ctx, dcaches[l], HKV, D, kd[0, l], vd[0, l], cu1, B, 1)
+                if events is not None:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                # the cached mask is known on the host after prefill: SA layers are sized for sinks + window
+                bound = cur["n"] if mask[l] else min(cur["n"], NS + W)
+                F.flux_attn_decode(ctx, cfg, qd[0, l], bound, dcaches[l], dmodes[int(mask[l])], outd)
+                if events is not None:
+                    e1.record()
+                    events.append((int(mask[l]), e0, e1))
+
+        def time_decode(mask, steps, warmup, events=None):
+            for _ in range(warmup):
+                decode_step(mask)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                decode_step(mask, events)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps
+
+        ev = []
+        half = max(1, args.decode_steps // 2)
+        td_mix = time_decode(mask_d, args.decode_steps, args.decode_warmup, ev)
+        fa_ms = [a.elapsed_time(b) for m, a, b in ev if m == 1]
+        sa_ms = [a.elapsed_time(b) for m, a, b in ev if m == 0]
+        kv_len.fill_(N)
+        cur["n"] = N
+        td_fa = time_decode(np.ones(LD, dtype=np.uint8), half, 2)
+        fa_avg = sum(fa_ms) / max(len(fa_ms), 1)
+        sa_avg = sum(sa_ms) / max(len(sa_ms), 1)
+        n_mid = N + args.decode_warmup + args.decode_steps // 2
+        bytes_fa = 2.0 * B * n_mid * HKV * D * 2 + 2.0 * B * HQ * D * 2         # K and V rows once + q + out
+        bytes_sa = 2.0 * B * (NS + W) * HKV * D * 2 + 2.0 * B * HQ * D * 2
+        n_fa = int(mask_d.sum())
+        ach = bytes_fa / (fa_avg * 1e-3) / 1e9
+        decode = {
+            "workload": "long-context decode: %d layers, batch %d, %d cached tokens, %d/%d heads, D %d, "
+                        "%d of %d layers SA (%d sinks + %d window), seed %d" % (LD, B, N, HQ, HKV, D, LD - n_fa, LD, NS, W, SEED_D),
+            "ms_per_step_mix": td_mix * 1e3, "ms_per_step_all_fa": td_fa * 1e3,
+            "speedup_mix_vs_all_fa": td_fa / td_mix,
+            "predicted_speedup_from_bytes": (LD * bytes_fa) / (n_fa * bytes_fa + (LD - n_fa) * bytes_sa),
+            "fa_layer_ms": fa_avg, "sa_layer_ms": sa_avg,
+            "roofline": {"kernel": "decode_splitk_kernel<128> + decode_combine_kernel<128> (FA layers)",
+                         "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": bytes_fa,
+                         "launch_ms": fa_avg},
+            "sa_achieved_gbs": bytes_sa / (sa_avg * 1e-3) / 1e9 if sa_ms else None,
+        }
+        del kc, vc, dcaches
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ router (end-to-end routed workload shape)
+    lens = [8192, 32768, 65536, 131072] if not args.small else [512, 2048]
+    hidden, inner, pool = 4096, 256, 100
+    T = sum(lens)
+    x = torch.empty(1, 1, T, hidden, dtype=torch.bfloat16, device=dev)
+    synth_gpu.fill_normal_bf16(x, 4, synth.stream_id(synth.STREAM_X))
+    w1 = torch.empty(1, 1, inner, hidden, dtype=torch.bfloat16, device=dev)
+    w2 = torch.empty(1, 1, 2, inner, dtype=torch.bfloat16, device=dev)
+    s02 = torch.full((1,), 0.02, dtype=torch.float32, device=dev)
+    synth_gpu.fill_normal_bf16(w1, 4, synth.stream_id(synth.STREAM_W1), s02, 0)
+    synth_gpu.fill_normal_bf16(w2, 4, synth.stream_id(synth.STREAM_W2), s02, 0)
+    cu_r = i32([0] + list(np.cumsum(lens)))
+    mode_r = torch.zeros(len(lens), dtype=torch.uint8, device=dev)
+    for _ in range(10):
+        F.flux_router(ctx, x, cu_r, len(lens), hidden, pool, w1, None, w2, None, inner, mode_r)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(200):
+        F.flux_router(ctx, x, cu_r, len(lens), hidden, pool, w1, None, w2, None, inner, mode_r)
+    torch.cuda.synchronize()
+    router = {"us_per_layer_call": (time.perf_counter() - t0) / 200 * 1e6, "batch": len(lens), "pool": pool,
+              "hidden": hidden, "inner": inner, "paper_ms_per_layer": 0.20}
+
+    status = F.flux_last_device_status(ctx)
+    F.flux_destroy(ctx)
+
+    t_step = prefill["ms_per_step_mix"] if prefill else None
+    line = {
+        "metric": "prefill tokens/s and decode ms/step at 1 MI355X; speedup vs all-FA; % MFMA / HBM peak",
+        "value": prefill["tokens_per_s_mix"] if prefill else None,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "stack prefill: %d layers, batch 1, seq_len %d, %d/%d heads, D %d, bf16 N(0,1) x per-head "
+                               "U(0.5,2) scales, seed %d, %d of %d layers SA (%d sinks + %d window), fp32 accumulate"
+                               % (L, S, HQ, HKV, D, SEED, N_SA, L, NS, W),
+                   "layers": L, "batch": 1, "seq_len": S, "n_q_heads": HQ, "n_kv_heads": HKV, "head_dim": D,
+                   "n_sink": NS, "window": W, "sa_layers": N_SA},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "prefill": prefill, "decode": decode, "router": router, "device_status": status,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -34,22 +34,39 @@ struct PrefillArgs {
 };
 
 constexpr int BM = 128;   // query rows per workgroup
-constexpr int BN = 64;    // keys per iteration
+constexpr float kRescaleThreshold = 8.0f;   // log2 units: rescale O only when the row max grew by > 2^8
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
-  constexpr int KC = D / 16;            // MFMA k-steps over the head dimension (QK^T)
-  constexpr int DB = D / 32;            // 32-wide output blocks over the head dimension (PV)
-  constexpr int CPR = D / 8;            // 16-byte chunks per row
-  constexpr int NLD = BN * CPR / 256;   // 16-byte chunks per thread per tile
-  constexpr int KROW = D + 8;           // LDS row pitch of the K tile (elements): +16 B
-  constexpr int VROW = D + 32;          // LDS row pitch of the V tile (elements): +64 B
+// One wave-wide direct global -> LDS transfer: every lane fetches its own 16 bytes, the 64 pieces land
+// at lds_base + 16 * lane.  Issued as inline assembly so that the compiler does not serialise later LDS
+// reads of the OTHER stage behind it; completion is awaited explicitly with vmcnt(0) before the barrier.
+// M0 (the LDS base of the transfer) is written here and holds no other live value in these kernels.
+__device__ __forceinline__ void dma16(const char* base /*uniform*/, int lane_off, uint32_t lds_base /*uniform*/) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+}
 
-  __shared__ __attribute__((aligned(16))) __bf16 ks[BN * KROW];
-  __shared__ __attribute__((aligned(16))) __bf16 vs[BN * VROW];
+template <int D, int NKB>                 // NKB: 32-key blocks per iteration (BN = 32 * NKB keys)
+__global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillArgs a) {
+  constexpr int BN = 32 * NKB;
+  constexpr int KC = D / 16;              // MFMA k-steps over the head dimension (QK^T)
+  constexpr int DB = D / 32;              // 32-wide output blocks over the head dimension (PV)
+  constexpr int CPR = D / 8;              // 16-byte chunks per row
+  constexpr int ROWB = D * 2;             // bytes per K/V row
+  constexpr int KPITCH = ROWB + 16;       // K tile: rows padded by one chunk (conflict-free 16-byte reads)
+  constexpr int NKI = (BN * (CPR + 1) + 63) / 64;   // wave-wide 1 KB transfers per K tile (padding chunks included)
+  constexpr int NVI = BN * CPR / 64;         // wave-wide 1 KB transfers per V tile
+  constexpr int KTILE = NKI * 1024;       // bytes (whole transfers; the tail of the last one is unused)
+  constexpr int VTILE = BN * ROWB;        // V tile: unpadded rows, chunk index XOR-swizzled by the row
+  constexpr int STAGE = KTILE + VTILE;
+  constexpr int KPW = (NKI + 3) / 4;         // K transfers per wave (the last may be missing)
+  constexpr int VPW = (NVI + 3) / 4;         // V transfers per wave
+  constexpr int RPI = 64 / CPR;              // V rows per transfer
+  static_assert(BN * CPR % 64 == 0, "V tile must split into whole wave transfers");
+
+  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
 
   const int tid = threadIdx.x;
-  const int w = tid >> 6, l = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l = tid & 63;
   const int g = l >> 5, n = l & 31;
   const int qt = a.n_qtiles - 1 - (int)blockIdx.x;          // heavy tiles first
   const int h = blockIdx.y, b = blockIdx.z;
@@ -98,43 +115,78 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   }
   const int n_iter = n_a + n_b;
 
-  const __bf16* kbase = a.k + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
-  const __bf16* vbase = a.v + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
-  const int row_max = len - 1;                               // never read rows that were not appended
+  const char* kbase = (const char*)(a.k + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h);
+  const char* vbase = (const char*)(a.v + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h);
+  const int pitch_g = (int)a.stride_t * 2;                   // bytes between rows in the cache
 
-  u32x4 kpre[NLD], vpre[NLD];
-  auto load_tile = [&](int it) {
+  // ---- direct global -> LDS transfers.  One transfer moves 64 x 16 bytes to 1 KB of consecutive LDS;
+  // which (row, chunk) a lane fetches decides where that chunk lands.  Per lane, the row and chunk of
+  // each of this wave's transfers are fixed for the whole kernel.
+  // K: LDS slot p = 64*I + l of transfer I holds (row p/(CPR+1), chunk p%(CPR+1)); the padding slot of a
+  // row re-fetches its last chunk.  V: transfer I covers rows I*RPI .. +RPI-1; lane l sits at
+  // (row l/CPR, physical chunk l%CPR) and fetches the logical chunk that the swizzle maps there.
+  auto k_slot = [&](int t, int rmax) {
+    const int p = 64 * (w + 4 * t) + l;
+    return min(min(p / (CPR + 1), BN - 1), rmax) * pitch_g + min(p % (CPR + 1), CPR - 1) * 16;
+  };
+  const int v_lrow = l / CPR;
+  const int v_swz = D == 128 ? ((v_lrow & 3) << 2) : (((v_lrow >> 1) & 1) << 2);
+  const int v_chunk = (l % CPR) ^ v_swz;
+  auto v_slot = [&](int t, int rmax) { return min((w + 4 * t) * RPI + v_lrow, rmax) * pitch_g + v_chunk * 16; };
+  int k_off[KPW], v_off[VPW];                                // byte offsets inside a tile that is fully cached
+#pragma unroll
+  for (int t = 0; t < KPW; ++t) k_off[t] = k_slot(t, BN);
+#pragma unroll
+  for (int t = 0; t < VPW; ++t) v_off[t] = v_slot(t, BN);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(FLUX_LDS char*)smem;
+
+  auto issue_tile = [&](int it, int stage) {
     const int j0 = (it < n_a ? it : win0 + (it - n_a)) * BN;
+    const int rmax = len - 1 - j0;                           // rows past the cached length are clamped
+    const char* kt = kbase + (int64_t)j0 * pitch_g;
+    const char* vt = vbase + (int64_t)j0 * pitch_g;
+    const uint32_t lk = lds0 + stage * STAGE + 1024 * w;
+    const uint32_t lv = lk + KTILE;
+    const bool whole = rmax >= BN - 1;                       // uniform: only the last tile can be partial
+    if (whole) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int e = i * 256 + tid;
-      const int64_t row = min(j0 + e / CPR, row_max);
-      kpre[i] = *(const u32x4*)(kbase + row * a.stride_t + (e % CPR) * 8);
-      vpre[i] = *(const u32x4*)(vbase + row * a.stride_t + (e % CPR) * 8);
-    }
-  };
-  auto store_tile = [&]() {
+      for (int t = 0; t < KPW; ++t)
+        if (4 * t + 3 < NKI || w + 4 * t < NKI) dma16(kt, k_off[t], lk + 4096 * t);
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int e = i * 256 + tid;
-      *(u32x4*)(ks + (e / CPR) * KROW + (e % CPR) * 8) = kpre[i];
-      *(u32x4*)(vs + (e / CPR) * VROW + (e % CPR) * 8) = vpre[i];
+      for (int t = 0; t < VPW; ++t)
+        if (4 * t + 3 < NVI || w + 4 * t < NVI) dma16(vt, v_off[t], lv + 4096 * t);
+    } else {
+#pragma unroll
+      for (int t = 0; t < KPW; ++t)
+        if (4 * t + 3 < NKI || w + 4 * t < NKI) dma16(kt, k_slot(t, rmax), lk + 4096 * t);
+#pragma unroll
+      for (int t = 0; t < VPW; ++t)
+        if (4 * t + 3 < NVI || w + 4 * t < NVI) dma16(vt, v_slot(t, rmax), lv + 4096 * t);
     }
   };
 
-  float m_run = -INFINITY, l_run = 0.f;
+  // ---- per-lane LDS read offsets (bytes, relative to the stage)
+  const int k_rd = n * KPITCH + g * 16;                       // K fragment: row 32*kb + n, chunk 2*kc + g
+  const int s16 = l & 15, beta = (l >> 4) & 1;
+  const int v_xr = D == 128 ? (s16 >> 2) : ((s16 >> 3) & 1);
+  int v_rd[DB];                                              // V^T fragment for output block db
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    v_rd[db] = KTILE + (4 * g + (s16 >> 2)) * ROWB + ((db ^ v_xr) * 64) + (2 * beta + ((s16 & 3) >> 1)) * 16 + (s16 & 1) * 8;
+
+  float m_ref = -INFINITY, l_run = 0.f;                      // m_ref: the maximum the exponents refer to
   f32x16 o[DB];
 #pragma unroll
   for (int i = 0; i < DB; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
 
-  if (n_iter > 0) load_tile(0);
+  if (n_iter > 0) issue_tile(0, 0);
   for (int it = 0; it < n_iter; ++it) {
-    __syncthreads();                                         // previous tile fully consumed
-    store_tile();
-    __syncthreads();
-    if (it + 1 < n_iter) load_tile(it + 1);                  // in flight during the math below
+    const int stage = it & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this wave's transfers have landed
+    __syncthreads();                                         // ... and everyone's; the other stage is free
+    if (it + 1 < n_iter) issue_tile(it + 1, stage ^ 1);      // in flight during the math below
 
     const int j0 = (it < n_a ? it : win0 + (it - n_a)) * BN;
     // does this wave see anything in the block, and does it need the element mask?
@@ -144,51 +196,57 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       const bool all_sink = j0 + BN <= a.n_sink;
       if (!all_sink) {
         if (j0 >= a.n_sink && j0 + BN - 1 < i_w_min - a.window + 1) skip = true;   // before every window
-        if (i_w_max - j0 >= a.window) need_mask = true;                           // some row's window starts inside or after
+        if (i_w_max - j0 >= a.window) need_mask = true;                           // a window edge falls inside
       }
     }
     if (skip) continue;
 
+    FLUX_LDS char* st = (FLUX_LDS char*)smem + stage * STAGE;
     // ---- S^T = K Q^T
-    f32x16 s[2];
+    f32x16 s[NKB];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-      const __bf16* krow = ks + (32 * kb + n) * KROW + 8 * g;
+      bf16x8 kf[KC];
 #pragma unroll
-      for (int kc = 0; kc < KC; ++kc) {
-        const bf16x8 kf = *(const bf16x8*)(krow + 16 * kc);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kc], s[kb], 0, 0, 0);
-      }
+      for (int kc = 0; kc < KC; ++kc) kf[kc] = *(FLUX_LDS bf16x8*)(st + k_rd + 32 * kb * KPITCH + 32 * kc);
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kc], qf[kc], s[kb], 0, 0, 0);
     }
     if (need_mask) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
-          bool vis = j <= i_mine;
-          if (sa) vis = vis && (j < a.n_sink || i_mine - j < a.window);
-          if (!vis) s[kb][r] = -INFINITY;
+          const bool vis = (j <= i_mine) & (!sa | (j < a.n_sink) | (i_mine - j < a.window));
+          s[kb][r] = vis ? s[kb][r] : -INFINITY;
         }
     }
-    // ---- online softmax for this lane's query column
+    // ---- online softmax for this lane's query column, with lazy rescaling: the accumulators keep
+    // referring to m_ref until the running maximum has grown by more than 2^kRescaleThreshold
     float mloc = s[0][0];
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, s[0][r]);
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[1][r]);
+      for (int r = (kb == 0 ? 1 : 0); r < 16; ++r) mloc = fmaxf(mloc, s[kb][r]);
     mloc = max_across_halves(mloc);
-    const float m_new = fmaxf(m_run, mloc);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;    // a row that has seen no key yet
-    const float alpha = fast_exp2((m_run - m_use) * a.scale_log2);
-    const float mneg = -m_use * a.scale_log2;
-    m_run = m_new;
-    bf16x8 pf[2][2];
-    float psum = 0.f;
+    const float m_new = fmaxf(m_ref, mloc);
+    const bool grow = (m_new - m_ref) * a.scale_log2 > kRescaleThreshold;   // false while both are -inf
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+      const float alpha = fast_exp2((m_ref - m_new) * a.scale_log2);        // 0 on the first block
+      const float al = m_new == -INFINITY ? 1.f : alpha;
+      l_run *= al;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int db = 0; db < DB; ++db) o[db] *= al;
+      m_ref = m_new;
+    }
+    const float mneg = m_ref == -INFINITY ? 0.f : -m_ref * a.scale_log2;    // a row that has seen no key yet
+    bf16x8 pf[NKB][2];
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         uint32_t pk[4];
@@ -197,23 +255,21 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           const float p0 = fast_exp2(__builtin_fmaf(s[kb][8 * c + 2 * t], a.scale_log2, mneg));
           const float p1 = fast_exp2(__builtin_fmaf(s[kb][8 * c + 2 * t + 1], a.scale_log2, mneg));
           pk[t] = pack_bf16(p0, p1);
-          psum += bf16_lo(pk[t]) + bf16_hi(pk[t]);           // the denominator sums the rounded weights
+          // the denominator sums the same rounded weights the numerator uses
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[t]), ones, l_run, false);
         }
         pf[kb][c] = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int db = 0; db < DB; ++db) o[db] *= alpha;
     // ---- O^T += V^T P^T
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        const __bf16* vrow = vs + (32 * kb + 16 * c + 4 * g + ((l & 15) >> 2)) * VROW + 16 * ((l >> 4) & 1) + 4 * (l & 3);
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)(vrow + 32 * db));
-          const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)(vrow + 32 * db + 8 * VROW));
+          FLUX_LDS char* vp = st + v_rd[db] + (32 * kb + 16 * c) * ROWB;
+          const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)vp);
+          const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)(vp + 8 * ROWB));
           const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][c], o[db], 0, 0, 0);
         }
@@ -244,7 +300,6 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q, const int32_t* cu_q,
                           int max_q_len, int max_kv_len, const flux_kv_cache& cache, const uint8_t* mode,
                           void* out, hipStream_t s) {
-  (void)c;
   (void)max_kv_len;
   const float scale = cfg.softmax_scale != 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.head_dim);
   PrefillArgs a;
@@ -263,13 +318,19 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.n_sink = cfg.n_sink;
   a.window = cfg.window;
   a.n_qtiles = (max_q_len + BM - 1) / BM;
+  const int nkb = c.prefill_nkb;
   a.scale_log2 = scale * kLog2e;
   a.out_fp32 = cfg.out_dtype;
   a.out = out;
   if (a.n_qtiles == 0) return hipSuccess;
   const dim3 grid(a.n_qtiles, cfg.n_q_heads, cache.batch);
-  if (cfg.head_dim == 128) hipLaunchKernelGGL(prefill_kernel<128>, grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(prefill_kernel<64>, grid, dim3(256), 0, s, a);
+  if (cfg.head_dim == 128) {
+    if (nkb == 1) hipLaunchKernelGGL((prefill_kernel<128, 1>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(256), 0, s, a);
+  } else {
+    if (nkb == 1) hipLaunchKernelGGL((prefill_kernel<64, 1>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((prefill_kernel<64, 2>), grid, dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 

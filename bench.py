@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--decode-warmup", type=int, default=10)
     ap.add_argument("--only", choices=["all", "prefill", "decode"], default="all",
                     help="restrict the run (profiling); the JSON line then carries nulls for the rest")
+    ap.add_argument("--mask", choices=["mix", "all-fa", "all-sa"], default="mix",
+                    help="layer mask of the timed steps; all-fa / all-sa give single-kernel profiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="shrunken shapes for a quick functional check")
     return ap.parse_args()
@@ -67,6 +69,10 @@ def main():
         L, S, N_SA = 4, 4096, 2
     G = HQ // HKV
     mask_mix = synth.random_layer_mask(SEED, L, N_SA)            # 1 = FA, 0 = SA
+    if args.mask == "all-fa":
+        mask_mix = np.ones(L, dtype=np.uint8)
+    elif args.mask == "all-sa":
+        mask_mix = np.zeros(L, dtype=np.uint8)
     cfg = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 0)                 # bf16 output, as the paper's BF16 runs
 
     def pairs_fa(s):
@@ -135,10 +141,10 @@ def main():
             "tokens_per_s_all_fa": S / t_fa, "ms_per_step_all_fa": t_fa * 1e3,
             "speedup_mix_vs_all_fa": t_fa / t_mix, "predicted_speedup_from_flops": pred,
             "omega_msr": float((mask_mix == 0).mean()),
-            "fa_kernel_ms": fa_avg, "sa_kernel_ms": sa_avg,
+            "mask": args.mask, "fa_kernel_ms": fa_avg, "sa_kernel_ms": sa_avg,
             "sa_kernel_tflops": flops_sa / (sa_avg * 1e-3) / 1e12 if sa_ms else None,
         }
-        achieved = flops_fa / (fa_avg * 1e-3) / 1e12
+        achieved = flops_fa / (fa_avg * 1e-3) / 1e12 if fa_ms else 0.0
         roofline = {"kernel": "prefill_kernel<128> (FA layers)", "bound": "mfma", "achieved": achieved,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                     "traffic": None, "flops_per_launch": flops_fa, "launch_ms": fa_avg}
@@ -190,6 +196,10 @@ def main():
             LD, B, N = 4, 2, 16384
         cap = N + 2 * n_dec + 8
         mask_d = synth.random_layer_mask(SEED_D, LD, LD // 2)
+        if args.mask == "all-fa":
+            mask_d = np.ones(LD, dtype=np.uint8)
+        elif args.mask == "all-sa":
+            mask_d = np.zeros(LD, dtype=np.uint8)
         kc = torch.empty(LD, B, HKV, cap, D, dtype=torch.bfloat16, device=dev)
         vc = torch.empty(LD, B, HKV, cap, D, dtype=torch.bfloat16, device=dev)
         for l in range(LD):
@@ -248,7 +258,7 @@ def main():
         bytes_fa = 2.0 * B * n_mid * HKV * D * 2 + 2.0 * B * HQ * D * 2         # K and V rows once + q + out
         bytes_sa = 2.0 * B * (NS + W) * HKV * D * 2 + 2.0 * B * HQ * D * 2
         n_fa = int(mask_d.sum())
-        ach = bytes_fa / (fa_avg * 1e-3) / 1e9
+        ach = bytes_fa / (fa_avg * 1e-3) / 1e9 if fa_ms else 0.0
         decode = {
             "workload": "long-context decode: %d layers, batch %d, %d cached tokens, %d/%d heads, D %d, "
                         "%d of %d layers SA (%d sinks + %d window), seed %d" % (LD, B, N, HQ, HKV, D, LD - n_fa, LD, NS, W, SEED_D),

@@ -245,6 +245,8 @@ struct CombineArgs {
 template <int D>
 __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
   constexpr int RED = D + 2;
+  __shared__ float wgt[D];
+  __shared__ float red[4];
   const int d = threadIdx.x, head = blockIdx.x, b = blockIdx.y;
   int len = a.kv_len[b];
   len = len < 0 ? 0 : (len > a.capacity ? a.capacity : len);
@@ -252,14 +254,36 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
   const int n_vis = visible_len(len, a.mode[b], a.n_sink, a.window, sparse);
   const int nc = min((n_vis + a.chunk - 1) / a.chunk, a.n_chunks);   // chunks the launch covered
   const float* base = a.partials + ((int64_t)b * a.hq + head) * a.n_chunks * RED;
+  // ---- maximum over the chunks (threads take chunks round-robin, then a block reduction)
   float m = -INFINITY;
-  for (int c = 0; c < nc; ++c) m = fmaxf(m, base[c * RED + D]);
+  for (int c = d; c < nc; c += D) m = fmaxf(m, base[c * RED + D]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if ((d & 63) == 0) red[d >> 6] = m;
+  __syncthreads();
+  m = D == 128 ? fmaxf(red[0], red[1]) : red[0];
+  // ---- weights per chunk in LDS, D chunks at a time; every thread then sums its own column
   float num = 0.f, den = 0.f;
-  for (int c = 0; c < nc; ++c) {
-    const float wgt = fast_exp2((base[c * RED + D] - m) * a.scale_log2);
-    num += wgt * base[c * RED + d];
-    den += wgt * base[c * RED + D + 1];
+  for (int c0 = 0; c0 < nc; c0 += D) {
+    __syncthreads();
+    const int c = c0 + d;
+    float w = 0.f, l = 0.f;
+    if (c < nc) {
+      w = fast_exp2((base[c * RED + D] - m) * a.scale_log2);
+      l = base[c * RED + D + 1];
+    }
+    wgt[d] = w;
+    den += w * l;                                            // partial; reduced over the block below
+    __syncthreads();
+    const int cn = min(D, nc - c0);
+    for (int cc = 0; cc < cn; ++cc) num += wgt[cc] * base[(c0 + cc) * RED + d];
   }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off);
+  __syncthreads();
+  if ((d & 63) == 0) red[2 + (d >> 6)] = den;
+  __syncthreads();
+  den = D == 128 ? red[2] + red[3] : red[2];
   const float r = nc > 0 ? num / den : 0.f;                 // an empty cache yields zeros
   const int64_t off = ((int64_t)b * a.hq + head) * D + d;
   if (a.out_fp32) ((float*)a.out)[off] = r;
@@ -267,13 +291,13 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
 }
 
 DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len) {
-  // Aim for about 2048 workgroups (8 per CU) so the tail is short, with chunks of at least 256
-  // keys (64 per wave) so the per-chunk merge stays a small fraction of the streaming.
-  const long long pairs = (long long)batch * cfg.n_kv_heads;
+  // Aim for about 1024 workgroups (4 per CU, two rounds of the two that fit a CU) with chunks of at
+  // least 512 keys (128 per wave), so that the per-chunk merge stays a small fraction of the streaming.
+  const long long pairs = (long long)batch * cfg.n_kv_heads * ((cfg.n_q_heads / cfg.n_kv_heads + 15) / 16);
   long long total = pairs * (long long)(max_kv_len > 0 ? max_kv_len : 1);
-  long long chunk = (total + 2047) / 2048;
+  long long chunk = (total + 1023) / 1024;
   chunk = ((chunk + 127) / 128) * 128;
-  if (chunk < 256) chunk = 256;
+  if (chunk < 512) chunk = 512;
   DecodePlan p;
   p.chunk = (int)chunk;
   p.n_chunks = (int)(((long long)(max_kv_len > 0 ? max_kv_len : 1) + chunk - 1) / chunk);

@@ -75,8 +75,6 @@ int flux_create(flux_ctx** out, int device, size_t workspace_bytes) {
   if (!ctx) return FLUX_ENOMEM;
   memset(&ctx->c, 0, sizeof(ctx->c));
   ctx->c.device = device;
-  ctx->c.prefill_nkb = 2;
-  if (const char* e = getenv("FLUX_PREFILL_NKB")) ctx->c.prefill_nkb = atoi(e) == 1 ? 1 : 2;   // tuning knob
   if (device < 0) {   // no device: every call validates its arguments, then reports FLUX_EHIP
     *out = ctx;
     return FLUX_OK;

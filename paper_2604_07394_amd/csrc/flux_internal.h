@@ -32,7 +32,6 @@ struct Ctx {
   float* small;            // router scratch: pooled vectors and hidden activations
   float* partials;         // split-K partial results
   size_t partials_bytes;
-  int prefill_nkb;         // prefill tile shape: 32-key blocks per iteration (1 or 2)
 };
 
 constexpr int kCounters = 64;

@@ -2,14 +2,14 @@
 // and last `pool` token rows (App. C.1) -> Context Encoder Linear+SiLU -> Router Head Linear ->
 // argmax (tie to FA).  Everything after the bf16 loads is fp32; nothing is rounded in between.
 //
-// Two launches, both tiny and latency-bound:
+// Three launches, all tiny and latency-bound:
 //  1. router_pool: partial column sums of the pooled rows.  grid (column blocks, row splits, batch);
 //     a lane owns 8 adjacent columns (one 16-byte load per row), the 4 waves of a workgroup take
 //     different rows and are merged in LDS.  Row splits keep whole-sequence pooling (pool = 0) spread
 //     over the chip; with pool > 0 the cost is independent of the sequence length.
 //  2. router_mlp: grid (inner/8, batch); each wave produces two hidden units (dot of a bf16 W1 row
-//     with the pooled fp32 vector held in LDS).  The workgroup that arrives last (arrival counter)
-//     evaluates the two logits of every sequence in a fixed order and writes the decisions.
+//     with the pooled fp32 vector held in LDS) and applies SiLU.
+//  3. router_head: one wave per sequence turns the hidden vector into the two logits and the decision.
 #include "flux_internal.h"
 
 namespace flux {
@@ -66,14 +66,10 @@ struct MlpArgs {
   const __bf16* b2;
   float* hbuf;            // [batch, inner]
   int batch, hidden, inner, pool, splits;
-  uint32_t* counter;
-  uint8_t* mode_out;
-  float* logits_out;
 };
 
 __global__ __launch_bounds__(256) void router_mlp_kernel(MlpArgs a) {
   extern __shared__ float pvec[];                           // hidden floats
-  __shared__ int is_last;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
   const int b = blockIdx.y;
   const int n_rows = a.cu[b + 1] - a.cu[b];
@@ -109,41 +105,42 @@ __global__ __launch_bounds__(256) void router_mlp_kernel(MlpArgs a) {
       }
     }
   }
-  // ---- the last workgroup to arrive turns every sequence's hidden vector into logits
-  __syncthreads();
-  if (tid == 0) {
-    __threadfence();
-    const uint32_t prev = atomicAdd(a.counter, 1u);
-    is_last = (prev == gridDim.x * gridDim.y - 1);
+}
+
+struct HeadArgs {
+  const float* hbuf;      // [batch, inner]
+  const __bf16* w2;
+  const __bf16* b2;
+  int inner;
+  uint8_t* mode_out;
+  float* logits_out;
+};
+
+// Router Head: two dot products of length `inner` per sequence, then the hard decision.
+__global__ __launch_bounds__(64) void router_head_kernel(HeadArgs a) {
+  const int l = threadIdx.x, bb = blockIdx.x;
+  float s0 = 0.f, s1 = 0.f;
+  for (int j = l; j < a.inner; j += 64) {
+    const float hv = a.hbuf[(int64_t)bb * a.inner + j];
+    s0 = __builtin_fmaf((float)a.w2[j], hv, s0);
+    s1 = __builtin_fmaf((float)a.w2[a.inner + j], hv, s1);
   }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  for (int bb = w; bb < a.batch; bb += 4) {
-    float s0 = 0.f, s1 = 0.f;
-    for (int j = l; j < a.inner; j += 64) {
-      const float hv = a.hbuf[(int64_t)bb * a.inner + j];
-      s0 = __builtin_fmaf((float)a.w2[j], hv, s0);
-      s1 = __builtin_fmaf((float)a.w2[a.inner + j], hv, s1);
-    }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      s0 += __shfl_xor(s0, off);
-      s1 += __shfl_xor(s1, off);
+  for (int off = 32; off > 0; off >>= 1) {
+    s0 += __shfl_xor(s0, off);
+    s1 += __shfl_xor(s1, off);
+  }
+  if (l == 0) {
+    if (a.b2) {
+      s0 += (float)a.b2[0];
+      s1 += (float)a.b2[1];
     }
-    if (l == 0) {
-      if (a.b2) {
-        s0 += (float)a.b2[0];
-        s1 += (float)a.b2[1];
-      }
-      a.mode_out[bb] = s0 >= s1 ? 1 : 0;                     // argmax, tie -> index 0 = FA
-      if (a.logits_out) {
-        a.logits_out[2 * bb] = s0;
-        a.logits_out[2 * bb + 1] = s1;
-      }
+    a.mode_out[bb] = s0 >= s1 ? 1 : 0;                       // argmax, tie -> index 0 = FA
+    if (a.logits_out) {
+      a.logits_out[2 * bb] = s0;
+      a.logits_out[2 * bb + 1] = s1;
     }
   }
-  if (tid == 0) *a.counter = 0;
 }
 
 hipError_t launch_router(const Ctx& c, const void* x, const int32_t* cu_seqlens, int batch, int hidden, int pool,
@@ -178,10 +175,12 @@ hipError_t launch_router(const Ctx& c, const void* x, const int32_t* cu_seqlens,
   ma.inner = inner;
   ma.pool = pool;
   ma.splits = splits;
-  ma.counter = c.counters + 1;
-  ma.mode_out = mode_out;
-  ma.logits_out = logits_out;
   hipLaunchKernelGGL(router_mlp_kernel, dim3((inner + 7) / 8, batch), dim3(256), hidden * sizeof(float), s, ma);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  HeadArgs ha{hbuf, (const __bf16*)w2, (const __bf16*)b2, inner, mode_out, logits_out};
+  hipLaunchKernelGGL(router_head_kernel, dim3(batch), dim3(64), 0, s, ha);
   return hipGetLastError();
 }
 

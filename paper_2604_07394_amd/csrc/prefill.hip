@@ -25,7 +25,8 @@ struct PrefillArgs {
   const int32_t* kv_len;
   const uint8_t* mode;
   int capacity;
-  int hq, group;
+  int hq, hkv, group, batch;
+  int xcd_map;            // 0 plain, 1 pairs-per-XCD, 2 XCDs-per-pair (see the kernel)
   int n_sink, window;
   int n_qtiles;
   float scale_log2;
@@ -68,8 +69,36 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l = tid & 63;
   const int g = l >> 5, n = l & 31;
-  const int qt = a.n_qtiles - 1 - (int)blockIdx.x;          // heavy tiles first
-  const int h = blockIdx.y, b = blockIdx.z;
+  // ---- which (sequence, head, query tile) this workgroup owns.  Workgroups go to the 8 XCDs round-robin
+  // by linear id, and each XCD has its own L2.  All query heads and query tiles that read one
+  // (sequence, KV head) pair are therefore given ids of one residue mod 8, heaviest tiles first and the
+  // heads of a group next to each other, so that the workgroups resident on an XCD walk the same K/V
+  // rows at the same time and the rows come from HBM once per XCD instead of once per workgroup.
+  int qt, h, b;
+  {
+    const int i = blockIdx.x;
+    const int n_pairs = a.batch * a.hkv;
+    if (a.xcd_map == 1) {                                    // n_pairs a multiple of 8: pairs x, x+8, ... on XCD x
+      const int x = i & 7, j = i >> 3, per = n_pairs >> 3;
+      const int g = j % a.group, r = (j / a.group) % per, qtd = j / (a.group * per);
+      const int pair = x + 8 * r;
+      b = pair / a.hkv;
+      h = (pair % a.hkv) * a.group + g;
+      qt = a.n_qtiles - 1 - qtd;
+    } else if (a.xcd_map == 2) {                             // n_pairs divides 8: 8 / n_pairs XCDs share a pair
+      const int x = i & 7, j = i >> 3, share = 8 / n_pairs;
+      const int pair = x % n_pairs, sl = x / n_pairs;
+      const int g = j % a.group, qtd = (j / a.group) * share + sl;
+      b = pair / a.hkv;
+      h = (pair % a.hkv) * a.group + g;
+      qt = a.n_qtiles - 1 - qtd;
+      if (qt < 0) return;                                    // padding of the last round (uniform)
+    } else {                                                 // any other shape: plain order, heavy tiles first
+      qt = a.n_qtiles - 1 - i % a.n_qtiles;
+      h = (i / a.n_qtiles) % a.hq;
+      b = i / (a.n_qtiles * a.hq);
+    }
+  }
   const int kvh = h / a.group;
 
   const int q_begin = a.cu_q[b];
@@ -314,7 +343,9 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.mode = mode;
   a.capacity = cache.capacity;
   a.hq = cfg.n_q_heads;
+  a.hkv = cfg.n_kv_heads;
   a.group = cfg.n_q_heads / cfg.n_kv_heads;
+  a.batch = cache.batch;
   a.n_sink = cfg.n_sink;
   a.window = cfg.window;
   a.n_qtiles = (max_q_len + BM - 1) / BM;
@@ -324,7 +355,21 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.out_fp32 = cfg.out_dtype;
   a.out = out;
   if (a.n_qtiles == 0) return hipSuccess;
-  const dim3 grid(a.n_qtiles, cfg.n_q_heads, cache.batch);
+  const long long n_pairs = (long long)cache.batch * cfg.n_kv_heads;
+  long long n_wg;
+  if (n_pairs % 8 == 0) {
+    a.xcd_map = 1;
+    n_wg = (long long)a.n_qtiles * cfg.n_q_heads * cache.batch;
+  } else if (8 % n_pairs == 0) {
+    a.xcd_map = 2;
+    const long long share = 8 / n_pairs;
+    n_wg = 8 * a.group * ((a.n_qtiles + share - 1) / share);
+  } else {
+    a.xcd_map = 0;
+    n_wg = (long long)a.n_qtiles * cfg.n_q_heads * cache.batch;
+  }
+  if (n_wg > 0x7FFFFFFFll) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)n_wg);
   if (cfg.head_dim == 128) {
     if (nkb == 1) hipLaunchKernelGGL((prefill_kernel<128, 1>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(256), 0, s, a);

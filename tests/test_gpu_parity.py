@@ -179,10 +179,11 @@ def test_prefill_tiny_config_full_compare(F, ctx):
     print("tiny worst (max-abs, rel-L2):", worst)
 
 
-@pytest.mark.parametrize("d,hq,hkv", [(128, 8, 2), (128, 7, 1), (64, 4, 4)])
+@pytest.mark.parametrize("d,hq,hkv", [(128, 8, 2), (128, 7, 1), (64, 4, 4), (128, 6, 3)])
 def test_prefill_ragged_multi_tile(F, ctx, d, hq, hkv):
     """Ragged batch over several 128-row tiles with ragged tails, per-sequence modes, sinks and a
-    window that are not multiples of the 64-key block, per-head scales up to 2."""
+    window that are not multiples of the 64-key block, per-head scales up to 2.  The four shapes give
+    8, 4, 16 and 12 (sequence, KV head) pairs: every workgroup-to-XCD mapping of the kernel is used."""
     lens = [700, 129, 64, 1]
     modes = [SA, FA, SA, SA]
     lay = Layer(F, ctx, 21, 4, hq, hkv, d, 704, 37, 150, scales=True)

@@ -41,6 +41,18 @@ def parse():
     return ap.parse_args()
 
 
+def measured_traffic(key):
+    """HBM bytes per launch recorded under profiles/ from rocprofv3 counter runs (None if absent)."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")):
+            f = line.split()
+            if len(f) == 5 and f[0] == key:
+                return float(f[2]) + float(f[4])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -131,15 +143,16 @@ def main():
         t_mix = time_steps(mask_mix, args.steps, args.warmup, ev)
         fa_ms = [a.elapsed_time(b) for m, a, b in ev if m == 1]
         sa_ms = [a.elapsed_time(b) for m, a, b in ev if m == 0]
-        t_fa = time_steps(np.ones(L, dtype=np.uint8), max(1, args.steps // 2), 1)
+        # the all-FA comparison pass (skipped in single-mode profiling runs)
+        t_fa = time_steps(np.ones(L, dtype=np.uint8), max(1, args.steps // 2), 1) if args.mask == "mix" else None
         fa_avg = sum(fa_ms) / max(len(fa_ms), 1)
         sa_avg = sum(sa_ms) / max(len(sa_ms), 1)
         n_fa = int(mask_mix.sum())
         pred = (L * flops_fa) / (n_fa * flops_fa + (L - n_fa) * flops_sa)
         prefill = {
             "tokens_per_s_mix": S / t_mix, "ms_per_step_mix": t_mix * 1e3,
-            "tokens_per_s_all_fa": S / t_fa, "ms_per_step_all_fa": t_fa * 1e3,
-            "speedup_mix_vs_all_fa": t_fa / t_mix, "predicted_speedup_from_flops": pred,
+            "tokens_per_s_all_fa": S / t_fa if t_fa else None, "ms_per_step_all_fa": t_fa * 1e3 if t_fa else None,
+            "speedup_mix_vs_all_fa": t_fa / t_mix if t_fa else None, "predicted_speedup_from_flops": pred,
             "omega_msr": float((mask_mix == 0).mean()),
             "mask": args.mask, "fa_kernel_ms": fa_avg, "sa_kernel_ms": sa_avg,
             "sa_kernel_tflops": flops_sa / (sa_avg * 1e-3) / 1e12 if sa_ms else None,
@@ -147,7 +160,9 @@ def main():
         achieved = flops_fa / (fa_avg * 1e-3) / 1e12 if fa_ms else 0.0
         roofline = {"kernel": "prefill_kernel<128> (FA layers)", "bound": "mfma", "achieved": achieved,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                    "traffic": None, "flops_per_launch": flops_fa, "launch_ms": fa_avg}
+                    "traffic": measured_traffic("prefill_fa_stack_prefill_32768") if not args.small else None,
+                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
+                    "flops_per_launch": flops_fa, "launch_ms": fa_avg}
 
         # ---- CPU oracle on a bounded sample of the same workload (rank 0, N = 1)
         if not args.no_cpu_baseline:
@@ -251,7 +266,7 @@ def main():
         sa_ms = [a.elapsed_time(b) for m, a, b in ev if m == 0]
         kv_len.fill_(N)
         cur["n"] = N
-        td_fa = time_decode(np.ones(LD, dtype=np.uint8), half, 2)
+        td_fa = time_decode(np.ones(LD, dtype=np.uint8), half, 2) if args.mask == "mix" else None
         fa_avg = sum(fa_ms) / max(len(fa_ms), 1)
         sa_avg = sum(sa_ms) / max(len(sa_ms), 1)
         n_mid = N + args.decode_warmup + args.decode_steps // 2
@@ -262,13 +277,15 @@ def main():
         decode = {
             "workload": "long-context decode: %d layers, batch %d, %d cached tokens, %d/%d heads, D %d, "
                         "%d of %d layers SA (%d sinks + %d window), seed %d" % (LD, B, N, HQ, HKV, D, LD - n_fa, LD, NS, W, SEED_D),
-            "ms_per_step_mix": td_mix * 1e3, "ms_per_step_all_fa": td_fa * 1e3,
-            "speedup_mix_vs_all_fa": td_fa / td_mix,
+            "ms_per_step_mix": td_mix * 1e3, "ms_per_step_all_fa": td_fa * 1e3 if td_fa else None,
+            "speedup_mix_vs_all_fa": td_fa / td_mix if td_fa else None,
             "predicted_speedup_from_bytes": (LD * bytes_fa) / (n_fa * bytes_fa + (LD - n_fa) * bytes_sa),
             "fa_layer_ms": fa_avg, "sa_layer_ms": sa_avg,
             "roofline": {"kernel": "decode_splitk_kernel<128> + decode_combine_kernel<128> (FA layers)",
                          "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": bytes_fa,
+                         "frac": ach / PEAK_HBM_GBS,
+                         "traffic": measured_traffic("decode_fa_long_context_131072") if not args.small else None,
+                         "bytes_per_launch": bytes_fa,
                          "launch_ms": fa_avg},
             "sa_achieved_gbs": bytes_sa / (sa_avg * 1e-3) / 1e9 if sa_ms else None,
         }

@@ -1,0 +1,283 @@
+"""GPU parity at the full configuration sizes, in the launch configuration bench.py times, on sampled
+outputs that the fp64 oracle computes one by one (`attention_row`: one query position of one KV group
+against its whole visible history).
+
+Inputs are filled on the device by the seeded generator (libflux_synth.so, bit-identical to synth.py, see
+test_device_generator_matches_host_bits) and the rows the oracle needs are copied back from those input
+tensors; no expected value comes from the library under test.  Sampled positions always include the rows
+where the mask changes shape: 0, n_sink-1, n_sink, window-1, window, window+n_sink-1, window+n_sink, the
+edges of the 128-row / 64-key tiles, and the last row.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flux_oracle as O
+from paper_2604_07394_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+FA, SA = 1, 0
+
+
+@pytest.fixture(scope="module")
+def F():
+    from paper_2604_07394_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def G():
+    from paper_2604_07394_amd import synth_gpu
+    return synth_gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(F):
+    c = F.flux_create(0, 0)
+    yield c
+    F.flux_destroy(c)
+
+
+def i32(x):
+    return torch.tensor(x, dtype=torch.int32, device="cuda")
+
+
+def u8(x):
+    return torch.tensor(x, dtype=torch.uint8, device="cuda")
+
+
+def positions(n, n_sink, window, extra, seed):
+    """Sampled query positions of a sequence of n tokens."""
+    edge = [0, 1, n_sink - 1, n_sink, window - 1, window, window + n_sink - 1, window + n_sink,
+            63, 64, 127, 128, 255, 256, n // 2 - 1, n // 2, n - 129, n - 128, n - 2, n - 1]
+    rnd = np.random.default_rng(seed).integers(0, n, size=extra).tolist()
+    return sorted({int(p) for p in edge + rnd if 0 <= p < n})
+
+
+def check_rows(out, q, kf, vf, tok0, pos_list, kvh, group, mode, n_sink, window, pos0=0, what=""):
+    """Compare out rows (tok0 + p) of the heads of KV head kvh with the oracle; kf, vf are [n, D] fp64."""
+    worst = 0.0
+    num = den = 0.0
+    for p in pos_list:
+        qrow = H.torch_to_f64(q[tok0 + p, kvh * group:(kvh + 1) * group])
+        ref = O.attention_row(qrow, kf, vf, pos0 + p, mode, n_sink, window)
+        got = H.torch_to_f64(out[tok0 + p, kvh * group:(kvh + 1) * group])
+        assert np.isfinite(got).all(), f"{what}: non-finite output at position {p}"
+        d = np.abs(got - ref)
+        worst = max(worst, float(d.max()))
+        num += float((d ** 2).sum())
+        den += float((ref ** 2).sum())
+        assert d.max() <= H.MAX_ABS, f"{what}: position {p} kv head {kvh}: max-abs {d.max():.3e}"
+    rel = (num / max(den, 1e-300)) ** 0.5
+    assert rel <= H.REL_L2, f"{what}: rel-L2 {rel:.3e}"
+    return worst, rel
+
+
+def scales(seed, layer, hq, hkv):
+    qs = synth.head_scales(seed, synth.stream_id(synth.STREAM_QSCALE, layer), hq)
+    ks = synth.head_scales(seed, synth.stream_id(synth.STREAM_KSCALE, layer), hkv)
+    vs = synth.head_scales(seed, synth.stream_id(synth.STREAM_VSCALE, layer), hkv)
+    return [torch.from_numpy(x).cuda() for x in (qs, ks, vs)]
+
+
+def test_stack_prefill_shape_fa_and_sa_layers(F, G, ctx):
+    """Stack-prefill workload, one FA and one SA layer exactly as bench.py launches them:
+    batch 1, 32768 tokens, 32/8 heads, D 128, per-head scales U(0.5, 2), 128 sinks + 4096 window."""
+    S, HQ, HKV, D, NS, W, SEED = 32768, 32, 8, 128, 128, 4096, 1
+    mask = synth.random_layer_mask(SEED, 32, 16)
+    cfg32 = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 1)
+    cfg16 = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 0)
+    cu = i32([0, S])
+    for mode in (FA, SA):
+        layer = int(np.nonzero(mask == mode)[0][0])
+        qs, ks, vs = scales(SEED, layer, HQ, HKV)
+        q = torch.empty(1, S, HQ, D, dtype=torch.bfloat16, device="cuda")
+        kn = torch.empty(1, S, HKV, D, dtype=torch.bfloat16, device="cuda")
+        vn = torch.empty(1, S, HKV, D, dtype=torch.bfloat16, device="cuda")
+        G.fill_normal_bf16(q, SEED, synth.stream_id(synth.STREAM_Q, layer), qs, 2)
+        G.fill_normal_bf16(kn, SEED, synth.stream_id(synth.STREAM_K, layer), ks, 2)
+        G.fill_normal_bf16(vn, SEED, synth.stream_id(synth.STREAM_V, layer), vs, 2)
+        cache = F.KVCache.empty(1, HKV, S, D)
+        md = u8([mode])
+        F.flux_kv_append(ctx, cache, HKV, D, kn[0], vn[0], cu, S, S)
+        out32 = torch.full((S, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
+        out16 = torch.empty(S, HQ, D, dtype=torch.bfloat16, device="cuda")
+        F.flux_attn_prefill(ctx, cfg32, q[0], cu, S, S, cache, md, out32)
+        F.flux_attn_prefill(ctx, cfg16, q[0], cu, S, S, cache, md, out16)      # bench.py's output type
+        torch.cuda.synchronize()
+        assert int(cache.kv_len[0]) == S
+        # the bf16 output is the fp32 output rounded once, everywhere
+        assert torch.equal(out16, out32.to(torch.bfloat16))
+        pos = positions(S, NS, W, 24, 100 + mode)
+        for kvh in (0, 5):
+            kf = H.torch_to_f64(kn[0, :, kvh])
+            vf = H.torch_to_f64(vn[0, :, kvh])
+            w = check_rows(out32, q[0], kf, vf, 0, pos, kvh, HQ // HKV, mode, NS, W, what=f"stack prefill mode {mode}")
+            print("stack prefill mode", mode, "kv head", kvh, "worst max-abs %.2e rel-L2 %.2e" % w)
+        del q, kn, vn, cache, out32, out16
+        torch.cuda.empty_cache()
+
+
+def test_long_context_decode_shape_one_layer(F, G, ctx):
+    """Long-context decode workload, one layer as bench.py launches it: batch 8, 131072 cached tokens,
+    32/8 heads, D 128; one new row is appended, then FA (whole cache) and SA (128 sinks + 4096 window,
+    launch sized for the sparse list) decode."""
+    B, N, HQ, HKV, D, NS, W, SEED = 8, 131072, 32, 8, 128, 128, 4096, 2
+    cap = N + 8
+    kc = torch.empty(B, HKV, cap, D, dtype=torch.bfloat16, device="cuda")
+    vc = torch.empty(B, HKV, cap, D, dtype=torch.bfloat16, device="cuda")
+    G.fill_normal_bf16(kc[:, :, :N], SEED, synth.stream_id(synth.STREAM_K, 0))
+    G.fill_normal_bf16(vc[:, :, :N], SEED, synth.stream_id(synth.STREAM_V, 0))
+    kv_len = torch.full((B,), N, dtype=torch.int32, device="cuda")
+    cache = F.KVCache(kc, vc, kv_len)
+    qd = torch.empty(1, 1, B * HQ, D, dtype=torch.bfloat16, device="cuda")
+    kd = torch.empty(1, 1, B * HKV, D, dtype=torch.bfloat16, device="cuda")
+    vd = torch.empty(1, 1, B * HKV, D, dtype=torch.bfloat16, device="cuda")
+    G.fill_normal_bf16(qd, SEED, synth.stream_id(synth.STREAM_QDEC))
+    G.fill_normal_bf16(kd, SEED, synth.stream_id(synth.STREAM_KDEC))
+    G.fill_normal_bf16(vd, SEED, synth.stream_id(synth.STREAM_VDEC))
+    F.flux_kv_append(ctx, cache, HKV, D, kd[0, 0], vd[0, 0], i32(list(range(B + 1))), B, 1)
+    cfg = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 1)
+    out = {}
+    for mode, bound in ((FA, N + 1), (SA, NS + W)):
+        o = torch.full((B, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
+        F.flux_attn_decode(ctx, cfg, qd[0, 0], bound, cache, u8([mode] * B), o)
+        out[mode] = o
+    torch.cuda.synchronize()
+    assert kv_len.cpu().tolist() == [N + 1] * B
+    # the appended row landed at position N of every (sequence, KV head)
+    assert torch.equal(kc[:, :, N].reshape(B * HKV, D), kd[0, 0]) and torch.equal(vc[:, :, N].reshape(B * HKV, D), vd[0, 0])
+    q = qd[0, 0].view(B, HQ, D)
+    g = HQ // HKV
+    for b, kvh in ((0, 0), (3, 5), (7, 7), (5, 2)):
+        kf = H.torch_to_f64(kc[b, kvh, :N + 1])
+        vf = H.torch_to_f64(vc[b, kvh, :N + 1])
+        for mode in (FA, SA):
+            ref = O.attention_row(H.torch_to_f64(q[b, kvh * g:(kvh + 1) * g]), kf, vf, N, mode, NS, W)
+            got = H.torch_to_f64(out[mode][b, kvh * g:(kvh + 1) * g])
+            e = H.assert_close(got, ref, f"long decode seq {b} kv head {kvh} mode {mode}")
+            print("long decode", b, kvh, mode, "max-abs %.2e rel-L2 %.2e" % e)
+    assert F.flux_last_device_status(ctx) == 0
+
+
+def test_high_sparsity_prefill_shape(F, G, ctx):
+    """High-sparsity prefill workload, one SA and one FA layer: batch 2, 65536 tokens, 28/4 heads (group
+    of 7), D 128, 64 sinks + 2048 window, seed 3."""
+    B, S, HQ, HKV, D, NS, W, SEED = 2, 65536, 28, 4, 128, 64, 2048, 3
+    q = torch.empty(1, B * S, HQ, D, dtype=torch.bfloat16, device="cuda")
+    kn = torch.empty(1, B * S, HKV, D, dtype=torch.bfloat16, device="cuda")
+    vn = torch.empty(1, B * S, HKV, D, dtype=torch.bfloat16, device="cuda")
+    G.fill_normal_bf16(q, SEED, synth.stream_id(synth.STREAM_Q, 0))
+    G.fill_normal_bf16(kn, SEED, synth.stream_id(synth.STREAM_K, 0))
+    G.fill_normal_bf16(vn, SEED, synth.stream_id(synth.STREAM_V, 0))
+    cache = F.KVCache.empty(B, HKV, S, D)
+    cu = i32([0, S, 2 * S])
+    F.flux_kv_append(ctx, cache, HKV, D, kn[0], vn[0], cu, B * S, S)
+    cfg = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 1)
+    out = torch.full((B * S, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
+    for modes in ([SA, SA], [FA, SA]):
+        F.flux_attn_prefill(ctx, cfg, q[0], cu, S, S, cache, u8(modes), out)
+        torch.cuda.synchronize()
+        for b, kvh in ((0, 1), (1, 3)):
+            kf = H.torch_to_f64(kn[0, b * S:(b + 1) * S, kvh])
+            vf = H.torch_to_f64(vn[0, b * S:(b + 1) * S, kvh])
+            pos = positions(S, NS, W, 12, 7 + b)
+            w = check_rows(out, q[0], kf, vf, b * S, pos, kvh, HQ // HKV, modes[b], NS, W, what=f"high sparsity {modes} seq {b}")
+            print("high sparsity", modes, "seq", b, "worst max-abs %.2e rel-L2 %.2e" % w)
+
+
+def test_end_to_end_routed_ragged_batch(F, G, ctx):
+    """End-to-end routed workload, one layer: ragged batch 8192 / 32768 / 65536 / 131072, the router
+    (hidden 4096 -> 256 -> SiLU -> 2, weights N(0, 0.02), pooling 100 + 100 rows of the query tensor) decides
+    each sequence's mode on the device, prefill uses that mask without a host read-back, then two decode
+    steps reuse it."""
+    lens = [8192, 32768, 65536, 131072]
+    B, HQ, HKV, D, NS, W, SEED = 4, 32, 8, 128, 128, 4096, 4
+    hidden, inner, pool = HQ * D, 256, 100
+    T = sum(lens)
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    q = torch.empty(1, T, HQ, D, dtype=torch.bfloat16, device="cuda")
+    kn = torch.empty(1, T, HKV, D, dtype=torch.bfloat16, device="cuda")
+    vn = torch.empty(1, T, HKV, D, dtype=torch.bfloat16, device="cuda")
+    G.fill_normal_bf16(q, SEED, synth.stream_id(synth.STREAM_Q, 0))
+    G.fill_normal_bf16(kn, SEED, synth.stream_id(synth.STREAM_K, 0))
+    G.fill_normal_bf16(vn, SEED, synth.stream_id(synth.STREAM_V, 0))
+    w1 = torch.empty(1, 1, inner, hidden, dtype=torch.bfloat16, device="cuda")
+    w2 = torch.empty(1, 1, 2, inner, dtype=torch.bfloat16, device="cuda")
+    s02 = torch.full((1,), 0.02, dtype=torch.float32, device="cuda")
+    G.fill_normal_bf16(w1, SEED, synth.stream_id(synth.STREAM_W1), s02, 0)
+    G.fill_normal_bf16(w2, SEED, synth.stream_id(synth.STREAM_W2), s02, 0)
+    cu = i32(starts.tolist())
+    mode = torch.full((B,), 7, dtype=torch.uint8, device="cuda")
+    logits = torch.zeros(B, 2, dtype=torch.float32, device="cuda")
+    # the router reads the query tensor as [T, hidden] rows (Sec. 3.1)
+    F.flux_router(ctx, q, cu, B, hidden, pool, w1, None, w2, None, inner, mode, logits)
+    cap = max(lens) + 8
+    cache = F.KVCache.empty(B, HKV, cap, D)
+    F.flux_kv_append(ctx, cache, HKV, D, kn[0], vn[0], cu, T, max(lens))
+    cfg = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 1)
+    out = torch.full((T, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
+    F.flux_attn_prefill(ctx, cfg, q[0], cu, max(lens), max(lens), cache, mode, out)
+    torch.cuda.synchronize()
+    assert cache.kv_len.cpu().tolist() == lens
+
+    # ---- router against the oracle
+    x2d = q[0].view(T, hidden)
+    w1f, w2f = H.torch_to_f64(w1[0, 0]), H.torch_to_f64(w2[0, 0])
+    ref_modes = []
+    for b in range(B):
+        s, n = int(starts[b]), lens[b]
+        # only the rows the oracle's pooling selects are copied back; over them its mean takes every row
+        idx = O.pooled_rows(n, pool)
+        rows = x2d[s + torch.from_numpy(idx).cuda()]
+        ref_logits, ref_mode = O.router(H.torch_to_f64(rows), 0, w1f, None, w2f, None)
+        got = logits[b].cpu().numpy().astype(np.float64)
+        assert np.abs(got - ref_logits).max() < 1e-6, (b, got, ref_logits)
+        if abs(ref_logits[0] - ref_logits[1]) >= 1e-6:
+            assert int(mode[b]) == ref_mode
+        ref_modes.append(int(mode[b]))
+    print("routed modes", ref_modes, "logits", logits.cpu().numpy().round(5).tolist())
+    assert set(ref_modes) <= {FA, SA}
+
+    # ---- prefill rows under the routed mask, and the other mode for the longest sequence
+    g = HQ // HKV
+    for b, kvh in ((0, 0), (1, 3), (2, 6), (3, 1)):
+        s, n = int(starts[b]), lens[b]
+        kf = H.torch_to_f64(kn[0, s:s + n, kvh])
+        vf = H.torch_to_f64(vn[0, s:s + n, kvh])
+        w = check_rows(out, q[0], kf, vf, s, positions(n, NS, W, 8, 31 + b), kvh, g, ref_modes[b], NS, W,
+                       what=f"routed prefill seq {b}")
+        print("routed prefill seq", b, "mode", ref_modes[b], "worst max-abs %.2e rel-L2 %.2e" % w)
+    flipped = [1 - m for m in ref_modes]
+    F.flux_attn_prefill(ctx, cfg, q[0], cu, max(lens), max(lens), cache, u8(flipped), out)
+    torch.cuda.synchronize()
+    for b, kvh in ((3, 4), (0, 7)):
+        s, n = int(starts[b]), lens[b]
+        kf = H.torch_to_f64(kn[0, s:s + n, kvh])
+        vf = H.torch_to_f64(vn[0, s:s + n, kvh])
+        check_rows(out, q[0], kf, vf, s, positions(n, NS, W, 6, 41 + b), kvh, g, flipped[b], NS, W,
+                   what=f"flipped prefill seq {b}")
+
+    # ---- two decode steps with the cached decisions
+    for step in range(2):
+        qd = torch.empty(1, 1, B * HQ, D, dtype=torch.bfloat16, device="cuda")
+        kd = torch.empty(1, 1, B * HKV, D, dtype=torch.bfloat16, device="cuda")
+        vd = torch.empty(1, 1, B * HKV, D, dtype=torch.bfloat16, device="cuda")
+        G.fill_normal_bf16(qd, SEED, synth.stream_id(synth.STREAM_QDEC, 0, step))
+        G.fill_normal_bf16(kd, SEED, synth.stream_id(synth.STREAM_KDEC, 0, step))
+        G.fill_normal_bf16(vd, SEED, synth.stream_id(synth.STREAM_VDEC, 0, step))
+        F.flux_kv_append(ctx, cache, HKV, D, kd[0, 0], vd[0, 0], i32(list(range(B + 1))), B, 1)
+        od = torch.full((B, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
+        F.flux_attn_decode(ctx, cfg, qd[0, 0], max(lens) + step + 1, cache, mode, od)
+        torch.cuda.synchronize()
+        qv = qd[0, 0].view(B, HQ, D)
+        for b, kvh in ((0, 2), (3, 5)):
+            n = lens[b] + step + 1
+            kf = H.torch_to_f64(cache.k[b, kvh, :n])
+            vf = H.torch_to_f64(cache.v[b, kvh, :n])
+            ref = O.attention_row(H.torch_to_f64(qv[b, kvh * g:(kvh + 1) * g]), kf, vf, n - 1, ref_modes[b], NS, W)
+            H.assert_close(H.torch_to_f64(od[b, kvh * g:(kvh + 1) * g]), ref, f"routed decode step {step} seq {b}")
+    assert cache.kv_len.cpu().tolist() == [n + 2 for n in lens]
+    assert F.flux_last_device_status(ctx) == 0

@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--decode-steps", type=int, default=50)
     ap.add_argument("--decode-warmup", type=int, default=10)
-    ap.add_argument("--only", choices=["all", "prefill", "decode"], default="all",
+    ap.add_argument("--only", choices=["all", "prefill", "decode", "router"], default="all",
                     help="restrict the run (profiling); the JSON line then carries nulls for the rest")
     ap.add_argument("--mask", choices=["mix", "all-fa", "all-sa"], default="mix",
                     help="layer mask of the timed steps; all-fa / all-sa give single-kernel profiles")
@@ -305,14 +305,24 @@ def main():
     synth_gpu.fill_normal_bf16(w2, 4, synth.stream_id(synth.STREAM_W2), s02, 0)
     cu_r = i32([0] + list(np.cumsum(lens)))
     mode_r = torch.zeros(len(lens), dtype=torch.uint8, device=dev)
-    for _ in range(10):
-        F.flux_router(ctx, x, cu_r, len(lens), hidden, pool, w1, None, w2, None, inner, mode_r)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(200):
-        F.flux_router(ctx, x, cu_r, len(lens), hidden, pool, w1, None, w2, None, inner, mode_r)
-    torch.cuda.synchronize()
-    router = {"us_per_layer_call": (time.perf_counter() - t0) / 200 * 1e6, "batch": len(lens), "pool": pool,
+    def time_router(pool_rows, reps):
+        for _ in range(10):
+            F.flux_router(ctx, x, cu_r, len(lens), hidden, pool_rows, w1, None, w2, None, inner, mode_r)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(reps):
+            F.flux_router(ctx, x, cu_r, len(lens), hidden, pool_rows, w1, None, w2, None, inner, mode_r)
+        e1.record()
+        t_host = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3, t_host / reps * 1e6
+
+    us_pool, us_host = time_router(pool, 200)
+    us_full, _ = time_router(0, 20)          # the "Full" pooling point of App. D.2: mean over every row
+    router = {"us_per_layer_call": us_pool, "host_launch_us": us_host, "batch": len(lens), "pool": pool,
+              "us_per_layer_call_pool_all_rows": us_full, "rows_all": T,
               "hidden": hidden, "inner": inner, "paper_ms_per_layer": 0.20}
 
     status = F.flux_last_device_status(ctx)

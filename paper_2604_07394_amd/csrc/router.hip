@@ -37,9 +37,25 @@ __global__ __launch_bounds__(256) void router_pool_kernel(PoolArgs a) {
   const int n_pooled = all ? n_rows : 2 * a.pool;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (col < a.hidden) {
-    for (int t = split * 4 + w; t < n_pooled; t += 4 * a.splits) {
-      const int row = r0 + pooled_row(t, n_rows, a.pool, all);
-      const u32x4 v = *(const u32x4*)(a.x + (int64_t)row * a.hidden + col);
+    const __bf16* xc = a.x + (int64_t)r0 * a.hidden + col;
+    const int step = 4 * a.splits;
+    int t = split * 4 + w;
+    // four rows per round, so that four independent 16-byte loads are in flight per lane
+    for (; t + 3 * step < n_pooled; t += 4 * step) {
+      u32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        v[u] = *(const u32x4*)(xc + (int64_t)pooled_row(t + u * step, n_rows, a.pool, all) * a.hidden);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[2 * i] += bf16_lo(v[u][i]);
+          acc[2 * i + 1] += bf16_hi(v[u][i]);
+        }
+    }
+    for (; t < n_pooled; t += step) {
+      const u32x4 v = *(const u32x4*)(xc + (int64_t)pooled_row(t, n_rows, a.pool, all) * a.hidden);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         acc[2 * i] += bf16_lo(v[i]);
@@ -76,33 +92,51 @@ __global__ __launch_bounds__(256) void router_mlp_kernel(MlpArgs a) {
   const bool all = a.pool <= 0 || n_rows <= 2 * a.pool;
   const int n_pooled = all ? n_rows : 2 * a.pool;
   const float inv = n_pooled > 0 ? 1.0f / (float)n_pooled : 0.f;
-  for (int c = tid; c < a.hidden; c += 256) {
-    float s = 0.f;
-    for (int sp = 0; sp < a.splits; ++sp) s += a.psum[((int64_t)b * a.splits + sp) * a.hidden + c];
-    pvec[c] = s * inv;
+  // pooled mean: the row-split partial sums are added in split order (fixed, so the result is
+  // reproducible); 4 columns per thread and all splits' loads of a round in flight together
+  for (int c = tid * 4; c < a.hidden; c += 1024) {
+    const float* p = a.psum + (int64_t)b * a.splits * a.hidden + c;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    int sp = 0;
+    for (; sp + 8 <= a.splits; sp += 8) {
+      f32x4 v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = *(const f32x4*)(p + (int64_t)(sp + i) * a.hidden);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += v[i];
+    }
+    for (; sp < a.splits; ++sp) s += *(const f32x4*)(p + (int64_t)sp * a.hidden);
+    *(f32x4*)(pvec + c) = s * inv;
   }
   __syncthreads();
-  // two hidden units per wave
+  // two hidden units per wave, their weight rows streamed together
+  const int j0 = blockIdx.x * 8 + w * 2;
+  if (j0 < a.inner) {
+    const bool two = j0 + 1 < a.inner;
+    const __bf16* wrow0 = a.w1 + (int64_t)j0 * a.hidden;
+    const __bf16* wrow1 = wrow0 + (two ? a.hidden : 0);
+    float acc0 = 0.f, acc1 = 0.f;
+    for (int c = l * 8; c < a.hidden; c += 512) {
+      const u32x4 v0 = *(const u32x4*)(wrow0 + c);
+      const u32x4 v1 = *(const u32x4*)(wrow1 + c);
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int j = blockIdx.x * 8 + w * 2 + u;
-    if (j < a.inner) {
-      const __bf16* wrow = a.w1 + (int64_t)j * a.hidden;
-      float acc = 0.f;
-      for (int c = l * 8; c < a.hidden; c += 512) {
-        const u32x4 v = *(const u32x4*)(wrow + c);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc = __builtin_fmaf(bf16_lo(v[i]), pvec[c + 2 * i], acc);
-          acc = __builtin_fmaf(bf16_hi(v[i]), pvec[c + 2 * i + 1], acc);
-        }
+      for (int i = 0; i < 4; ++i) {
+        acc0 = __builtin_fmaf(bf16_lo(v0[i]), pvec[c + 2 * i], acc0);
+        acc0 = __builtin_fmaf(bf16_hi(v0[i]), pvec[c + 2 * i + 1], acc0);
+        acc1 = __builtin_fmaf(bf16_lo(v1[i]), pvec[c + 2 * i], acc1);
+        acc1 = __builtin_fmaf(bf16_hi(v1[i]), pvec[c + 2 * i + 1], acc1);
       }
+    }
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-      if (l == 0) {
-        if (a.b1) acc += (float)a.b1[j];
-        a.hbuf[(int64_t)b * a.inner + j] = acc / (1.0f + expf(-acc));   // SiLU
-      }
+    for (int off = 32; off > 0; off >>= 1) {
+      acc0 += __shfl_xor(acc0, off);
+      acc1 += __shfl_xor(acc1, off);
+    }
+    if (l < 2 && (l == 0 || two)) {
+      float acc = l == 0 ? acc0 : acc1;
+      const int j = j0 + l;
+      if (a.b1) acc += (float)a.b1[j];
+      a.hbuf[(int64_t)b * a.inner + j] = acc / (1.0f + expf(-acc));   // SiLU
     }
   }
 }
@@ -146,9 +180,9 @@ __global__ __launch_bounds__(64) void router_head_kernel(HeadArgs a) {
 hipError_t launch_router(const Ctx& c, const void* x, const int32_t* cu_seqlens, int batch, int hidden, int pool,
                          const void* w1, const void* b1, const void* w2, const void* b2, int inner,
                          uint8_t* mode_out, float* logits_out, hipStream_t s) {
-  // row splits: ~32 pooled rows per workgroup when the count is known, 32 splits for whole-sequence
+  // row splits: ~32 pooled rows per workgroup when the count is known, 64 splits for whole-sequence
   // pooling, bounded by the scratch region
-  int splits = pool > 0 ? (2 * pool + 31) / 32 : 32;
+  int splits = pool > 0 ? (2 * pool + 31) / 32 : 64;
   const size_t per_split = (size_t)batch * hidden * sizeof(float);
   const size_t hbytes = (size_t)batch * inner * sizeof(float);
   size_t room = kSmallBytes - hbytes;

@@ -20,6 +20,9 @@ What it follows (paper sections / equations):
   ``Linear -> SiLU``, Router Head ``Linear`` to two logits ``(pi_FA, pi_SA)``,
   hard decision by argmax with ``r_hard = 0`` meaning SA.
 * Route once in prefill, reuse the decision for every decode step, Sec. 3.3.
+* Sparse-decode residency, Sec. 3.3: a sparse layer keeps only the K/V rows its
+  kernel needs (the sinks and the last ``window`` positions); ``RingKVCache``
+  stores exactly those and ``decode_step_ring`` attends over what is stored.
 * Model Sparsity Ratio, Eq. (3) of Sec. 2.3, at layer granularity.
 
 Conventions: ``mode`` 1 = FA, 0 = SA (the paper's ``r_hard``).  All arrays are
@@ -31,7 +34,10 @@ Pins (tests/test_oracle_pins.py): closed-form visible counts, window >= length
 equals FA, rows of P sum to one, constant-V and constant-K special cases, shift
 invariance, brute-force enumeration on 8-token cases, a textbook dense
 formula, GQA by head repetition, decode == last prefill row, a hand-computed
-router, argmax flip and tie.  No function here is parity-unpinned.
+router, argmax flip and tie; for the ring residency: stored positions against
+their closed form, equality with the full-cache SA decode step by step across
+several wrap-arounds, and compaction of a prompt against row-by-row appends.
+No function here is parity-unpinned.
 """
 from __future__ import annotations
 
@@ -164,6 +170,77 @@ def decode_step(cache: KVCache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndar
         cache.append(b, k_new[b][None], v_new[b][None])
         out[b] = attention(q[b][None], cache.k[b], cache.v[b], int(modes[b]), n_sink, window, scale)[0]
     return out
+
+
+# --------------------------------------------------------------------------- sparse-decode residency
+
+class RingKVCache:
+    """K/V storage of a SPARSE layer in the sparse-decode configuration of Sec. 3.3: per sequence
+    ``n_sink + window`` rows and nothing else.
+
+    Row ``p`` for ``p < n_sink`` holds position ``p`` for ever; position ``p >= n_sink`` is written
+    to row ``n_sink + (p - n_sink) % window`` and so overwrites the position that left the window.
+    ``pos[b][row]`` remembers which position a row holds (-1 = never written).
+    """
+
+    def __init__(self, batch: int, n_kv_heads: int, head_dim: int, n_sink: int, window: int):
+        self.n_sink, self.window = n_sink, window
+        rows = n_sink + window
+        self.k = [np.zeros((rows, n_kv_heads, head_dim)) for _ in range(batch)]
+        self.v = [np.zeros((rows, n_kv_heads, head_dim)) for _ in range(batch)]
+        self.pos = [np.full(rows, -1, dtype=np.int64) for _ in range(batch)]
+        self.len = [0] * batch
+
+    def row_of(self, p: int) -> int:
+        return p if p < self.n_sink else self.n_sink + (p - self.n_sink) % self.window
+
+    def append(self, b: int, k_new: np.ndarray, v_new: np.ndarray) -> None:
+        """Rows one after the other, each at the next position."""
+        for r in range(k_new.shape[0]):
+            p = self.len[b]
+            row = self.row_of(p)
+            self.k[b][row] = k_new[r]
+            self.v[b][row] = v_new[r]
+            self.pos[b][row] = p
+            self.len[b] = p + 1
+
+    def length(self, b: int) -> int:
+        return self.len[b]
+
+    def stored(self, b: int):
+        """(positions, K rows, V rows) of everything stored for sequence b, in position order."""
+        rows = np.nonzero(self.pos[b] >= 0)[0]
+        rows = rows[np.argsort(self.pos[b][rows])]
+        return self.pos[b][rows], self.k[b][rows], self.v[b][rows]
+
+
+def decode_step_ring(cache: RingKVCache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, scale=None) -> np.ndarray:
+    """One sparse-layer decode step on the minimal cache: append the new row, then the query at the
+    newest position attends to EVERY stored row (Eq. 2: they are exactly its visible set).
+
+    q [B, Hq, D], k_new/v_new [B, Hkv, D] -> out [B, Hq, D].
+    """
+    n_b, hq, d = q.shape
+    hkv = k_new.shape[1]
+    group = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty_like(q)
+    for b in range(n_b):
+        cache.append(b, k_new[b][None], v_new[b][None])
+        _, kk, vv = cache.stored(b)
+        for h in range(hq):
+            s = scale * (kk[:, h // group] @ q[b, h])
+            pr = np.exp(s - s.max())
+            out[b, h] = (pr / pr.sum()) @ vv[:, h // group]
+    return out
+
+
+def compact_to_ring(full: KVCache, ring: RingKVCache) -> None:
+    """After the prompt has been prefilled on full K/V (the decision is known only then), keep what
+    a sparse layer needs: the same state as appending the prompt to an empty ring row by row."""
+    for b in range(len(full.k)):
+        ring.append(b, full.k[b], full.v[b])
 
 
 # --------------------------------------------------------------------------- router

@@ -282,3 +282,63 @@ def test_bf16_widening_exact():
     assert vals[0] == 1.0 and vals[1] == -1.0 and vals[2] == 2.0 and vals[4] == 0.0
     assert vals[3] == 0.10009765625                      # 0x3DCD = 1.6015625 * 2**-4
     assert vals[5] == (2 - 2 ** -7) * 2.0 ** 127
+
+
+# ----------------------------------------------------------------------------- sparse-decode residency (Sec. 3.3)
+
+@pytest.mark.parametrize("n_sink,window", [(3, 5), (0, 4), (4, 1), (2, 7)])
+def test_ring_stores_exactly_the_visible_set(n_sink, window):
+    """After n appended rows the ring holds positions {0..n_sink-1} and {n-window..n-1}, each once,
+    never more than n_sink + window rows: the set Eq. (2) lets the newest position see."""
+    g = rng(30)
+    ring = O.RingKVCache(1, 1, 2, n_sink, window)
+    for n in range(1, 4 * (n_sink + window) + 3):
+        row = g.standard_normal((1, 1, 2))
+        ring.append(0, row, -row)
+        pos, kk, vv = ring.stored(0)
+        want = sorted(set(range(min(n_sink, n))) | set(range(max(n - window, 0), n)))
+        assert pos.tolist() == want
+        assert len(pos) == closed_form_visible(n - 1, n_sink, window) <= n_sink + window
+        assert np.array_equal(vv, -kk)                      # K and V of a position travel together
+        assert np.array_equal(kk[-1], row[0])               # the newest row is the last stored position
+
+
+def test_ring_decode_equals_full_cache_sa_decode_bit_for_bit():
+    """The minimal cache changes where rows live, not what is computed: step by step, across several
+    wrap-arounds of the ring, the output equals the SA decode step on the full history exactly."""
+    g = rng(31)
+    B, Hq, Hkv, D, n_sink, window = 2, 4, 2, 8, 3, 5
+    full = O.KVCache(B, Hkv, D)
+    ring = O.RingKVCache(B, Hkv, D, n_sink, window)
+    prompt = [g.standard_normal((4, Hkv, D)), g.standard_normal((11, Hkv, D))]   # one shorter, one longer than the ring
+    pv = [g.standard_normal(p.shape) for p in prompt]
+    for b in range(B):
+        full.append(b, prompt[b], pv[b])
+    O.compact_to_ring(full, ring)
+    assert [ring.length(b) for b in range(B)] == [4, 11]
+    for step in range(23):
+        q = g.standard_normal((B, Hq, D))
+        kn, vn = g.standard_normal((B, Hkv, D)), g.standard_normal((B, Hkv, D))
+        ref = O.decode_step(full, q, kn, vn, [SA, SA], n_sink, window)
+        got = O.decode_step_ring(ring, q, kn, vn)
+        assert np.allclose(got, ref, rtol=0, atol=1e-13), step
+    assert [ring.length(b) for b in range(B)] == [27, 34]
+
+
+def test_ring_compaction_equals_row_by_row_appends_and_bulk_append():
+    g = rng(32)
+    n_sink, window = 2, 4
+    k, v = g.standard_normal((17, 1, 3)), g.standard_normal((17, 1, 3))
+    full = O.KVCache(1, 1, 3)
+    full.append(0, k, v)
+    a = O.RingKVCache(1, 1, 3, n_sink, window)
+    O.compact_to_ring(full, a)
+    b_ = O.RingKVCache(1, 1, 3, n_sink, window)
+    for r in range(17):
+        b_.append(0, k[r:r + 1], v[r:r + 1])
+    c = O.RingKVCache(1, 1, 3, n_sink, window)
+    c.append(0, k[:9], v[:9])
+    c.append(0, k[9:], v[9:])
+    for other in (b_, c):
+        assert np.array_equal(a.pos[0], other.pos[0]) and np.array_equal(a.k[0], other.k[0]) and np.array_equal(a.v[0], other.v[0])
+    assert a.pos[0].tolist() == [0, 1, 14, 15, 16, 13]      # rows 2..5 hold the p with (p - 2) % 4 = 0..3

@@ -49,6 +49,7 @@ enum {
   FLUX_DEV_BAD_LENGTH = 2     /* a kv_len / cu_seqlens value was inconsistent and was clamped */
 };
 
+
 typedef struct flux_ctx flux_ctx;   /* opaque; owns ONLY its device workspace */
 
 /* Attention shape and the SA pattern of one call.
@@ -139,6 +140,37 @@ int flux_attn_prefill(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, co
  * launch for the sparse case. */
 int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int max_kv_len,
                      const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream);
+
+/* ---- Sparse-decode residency (Sec. 3.3 "Efficient Deployment": a sparse layer keeps only the minimal
+ * KV cache its kernel needs and never stores the rest of the history; retrieval layers keep everything).
+ *
+ * A RING cache is a flux_kv_cache read with these rules: capacity >= n_sink + window rows per
+ * (sequence, head); row p < n_sink holds position p; position p >= n_sink lives in row
+ * n_sink + (p - n_sink) % window, overwriting the position that has just left the window; kv_len[b] is the
+ * LOGICAL length (positions appended so far) and is not bounded by capacity.  The rows stored for a
+ * sequence are then exactly the keys Eq. 2 lets its newest position see.  n_sink and window must be the
+ * same in every call on one ring cache.  A ring cache serves decode only: the prompt is prefilled on a
+ * full cache (the decision exists only after the router has seen the prompt), then compacted. */
+
+/* flux_kv_append on a ring cache.  Same arguments as flux_kv_append plus the ring geometry.  Of the new
+ * rows of a sequence only those that are still resident after the call are written (sinks, and the last
+ * `window` positions), so any number of rows may be appended at once.  kv_len[b] += rows of b. */
+int flux_kv_append_ring(flux_ctx* ctx, const flux_kv_cache* ring, int n_kv_heads, int head_dim, int n_sink,
+                        int window, const void* k_new, const void* v_new, const int32_t* cu_new,
+                        int total_new, int max_new, void* stream);
+
+/* Copy what a sparse layer keeps from a full cache `src` (after prefill) into the ring cache `dst`:
+ * positions [0, n_sink) and [max(len - window, n_sink), len) of every sequence, len = src kv_len[b]
+ * (clamped to src capacity); sets dst kv_len[b] = len.  Same batch in both; src is not modified and may
+ * be reused for the next layer's prompt. */
+int flux_kv_compact_ring(flux_ctx* ctx, const flux_kv_cache* src, const flux_kv_cache* dst, int n_kv_heads,
+                         int head_dim, int n_sink, int window, void* stream);
+
+/* flux_attn_decode of a sparse layer on its ring cache: the query of sequence b sits at position
+ * kv_len[b] - 1 (append first) and attends to every stored row (Eq. 2).  No mode argument: a ring cache
+ * holds a sparse layer.  cfg->n_sink and cfg->window are the ring geometry. */
+int flux_attn_decode_ring(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const flux_kv_cache* ring,
+                          void* out, void* stream);
 
 #ifdef __cplusplus
 }

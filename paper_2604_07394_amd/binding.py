@@ -25,7 +25,8 @@ FLUX_DEV_KV_OVERFLOW, FLUX_DEV_BAD_LENGTH = 1, 2
 FA, SA = 1, 0
 
 EXPORTS = ["flux_create", "flux_destroy", "flux_strerror", "flux_workspace_needed", "flux_last_device_status",
-           "flux_router", "flux_kv_append", "flux_attn_prefill", "flux_attn_decode"]
+           "flux_router", "flux_kv_append", "flux_attn_prefill", "flux_attn_decode",
+           "flux_kv_append_ring", "flux_kv_compact_ring", "flux_attn_decode_ring"]
 
 
 class FluxAttnCfg(C.Structure):
@@ -62,6 +63,15 @@ _lib.flux_attn_prefill.restype = C.c_int
 _lib.flux_attn_decode.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_int, C.POINTER(FluxKVCache),
                                   C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.flux_attn_decode.restype = C.c_int
+_lib.flux_kv_append_ring.argtypes = [C.c_void_p, C.POINTER(FluxKVCache), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+_lib.flux_kv_append_ring.restype = C.c_int
+_lib.flux_kv_compact_ring.argtypes = [C.c_void_p, C.POINTER(FluxKVCache), C.POINTER(FluxKVCache), C.c_int, C.c_int,
+                                      C.c_int, C.c_int, C.c_void_p]
+_lib.flux_kv_compact_ring.restype = C.c_int
+_lib.flux_attn_decode_ring.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.POINTER(FluxKVCache),
+                                       C.c_void_p, C.c_void_p]
+_lib.flux_attn_decode_ring.restype = C.c_int
 
 
 class FluxError(RuntimeError):
@@ -168,3 +178,21 @@ def flux_attn_decode(ctx, cfg, q, max_kv_len, cache, mode, out, stream=None) -> 
     cs = _cache_struct(cache)
     _check(_lib.flux_attn_decode(ctx, C.byref(cfg), _ptr(q), max_kv_len, C.byref(cs), _ptr(mode), _ptr(out),
                                  _stream(stream)))
+
+
+def flux_kv_append_ring(ctx, ring, n_kv_heads, head_dim, n_sink, window, k_new, v_new, cu_new, total_new, max_new,
+                        stream=None) -> None:
+    cs = _cache_struct(ring)
+    _check(_lib.flux_kv_append_ring(ctx, C.byref(cs), n_kv_heads, head_dim, n_sink, window, _ptr(k_new), _ptr(v_new),
+                                    _ptr(cu_new), total_new, max_new, _stream(stream)))
+
+
+def flux_kv_compact_ring(ctx, src, dst, n_kv_heads, head_dim, n_sink, window, stream=None) -> None:
+    ss, ds = _cache_struct(src), _cache_struct(dst)
+    _check(_lib.flux_kv_compact_ring(ctx, C.byref(ss), C.byref(ds), n_kv_heads, head_dim, n_sink, window,
+                                     _stream(stream)))
+
+
+def flux_attn_decode_ring(ctx, cfg, q, ring, out, stream=None) -> None:
+    cs = _cache_struct(ring)
+    _check(_lib.flux_attn_decode_ring(ctx, C.byref(cfg), _ptr(q), C.byref(cs), _ptr(out), _stream(stream)))

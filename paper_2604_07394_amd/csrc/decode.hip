@@ -36,6 +36,7 @@ struct DecodeArgs {
   int qblocks;            // ceil(group / 16)
   int n_sink, window;
   int chunk, n_chunks;
+  int ring;               // != 0: the cache is a sink + ring store of a sparse layer, kv_len is logical, no mode bytes
   float scale_log2;       // softmax scale * log2(e)
   float* partials;        // [B, Hq, n_chunks, D + 2]
 };
@@ -66,13 +67,15 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   const int b = blockIdx.z;
 
   int len = a.kv_len[b];
-  len = len < 0 ? 0 : (len > a.capacity ? a.capacity : len);
+  len = len < 0 ? 0 : ((!a.ring && len > a.capacity) ? a.capacity : len);
   bool sparse;
-  const int n_vis = visible_len(len, a.mode[b], a.n_sink, a.window, sparse);
+  const int n_vis = visible_len(len, a.ring ? 0 : a.mode[b], a.n_sink, a.window, sparse);
   const int c0 = ci * a.chunk;
   if (c0 >= n_vis) return;                                  // uniform for the whole workgroup
   const int c1 = min(c0 + a.chunk, n_vis);
   const int tail0 = len - a.window - a.n_sink;              // list index p >= n_sink maps to key p + tail0
+  // ring store: that key sits in row n_sink + (p + tail0 - n_sink) % window = n_sink + (p - n_sink + ring0) % window
+  const int ring0 = (a.ring && sparse) ? tail0 % a.window : 0;
 
   const __bf16* kbase = a.k + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
   const __bf16* vbase = a.v + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
@@ -92,7 +95,10 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
 
   auto key_of = [&](int p) -> int64_t {
     p = p < c1 ? p : c1 - 1;                                // keep every address inside the chunk
-    return (sparse && p >= a.n_sink) ? (int64_t)p + tail0 : (int64_t)p;
+    if (!sparse || p < a.n_sink) return (int64_t)p;
+    if (!a.ring) return (int64_t)p + tail0;
+    const int x = p - a.n_sink + ring0;                     // < 2 * window
+    return (int64_t)a.n_sink + (x >= a.window ? x - a.window : x);
   };
 
   u32x4 kreg[2][KC], vreg[VL];
@@ -237,7 +243,7 @@ struct CombineArgs {
   const float* partials;
   const int32_t* kv_len;
   const uint8_t* mode;
-  int capacity, hq, n_sink, window, chunk, n_chunks, out_fp32;
+  int capacity, hq, n_sink, window, chunk, n_chunks, out_fp32, ring;
   float scale_log2;
   void* out;
 };
@@ -249,9 +255,9 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
   __shared__ float red[4];
   const int d = threadIdx.x, head = blockIdx.x, b = blockIdx.y;
   int len = a.kv_len[b];
-  len = len < 0 ? 0 : (len > a.capacity ? a.capacity : len);
+  len = len < 0 ? 0 : ((!a.ring && len > a.capacity) ? a.capacity : len);
   bool sparse;
-  const int n_vis = visible_len(len, a.mode[b], a.n_sink, a.window, sparse);
+  const int n_vis = visible_len(len, a.ring ? 0 : a.mode[b], a.n_sink, a.window, sparse);
   const int nc = min((n_vis + a.chunk - 1) / a.chunk, a.n_chunks);   // chunks the launch covered
   const float* base = a.partials + ((int64_t)b * a.hq + head) * a.n_chunks * RED;
   // ---- maximum over the chunks (threads take chunks round-robin, then a block reduction)
@@ -309,7 +315,7 @@ size_t decode_partials_bytes(const flux_attn_cfg& cfg, int batch, const DecodePl
 }
 
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
-                         const flux_kv_cache& cache, const uint8_t* mode, void* out, hipStream_t s) {
+                         const flux_kv_cache& cache, const uint8_t* mode, int ring, void* out, hipStream_t s) {
   const DecodePlan plan = plan_decode(cfg, cache.batch, max_kv_len);
   const float scale = cfg.softmax_scale != 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.head_dim);
   DecodeArgs a;
@@ -330,6 +336,7 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   a.window = cfg.window;
   a.chunk = plan.chunk;
   a.n_chunks = plan.n_chunks;
+  a.ring = ring;
   a.scale_log2 = scale * kLog2e;
   a.partials = c.partials;
   const dim3 grid(plan.n_chunks, cfg.n_kv_heads * a.qblocks, cache.batch);
@@ -349,6 +356,7 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   ca.chunk = plan.chunk;
   ca.n_chunks = plan.n_chunks;
   ca.out_fp32 = cfg.out_dtype;
+  ca.ring = ring;
   ca.scale_log2 = a.scale_log2;
   ca.out = out;
   const dim3 cgrid(cfg.n_q_heads, cache.batch);

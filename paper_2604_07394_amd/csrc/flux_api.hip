@@ -159,7 +159,7 @@ int flux_kv_append(flux_ctx* ctx, const flux_kv_cache* cache, int n_kv_heads, in
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
   if (total_new == 0) return FLUX_OK;
   const hipError_t e =
-      launch_kv_append(ctx->c, *cache, n_kv_heads, head_dim, k_new, v_new, cu_new, total_new, (hipStream_t)stream);
+      launch_kv_append(ctx->c, *cache, n_kv_heads, head_dim, k_new, v_new, cu_new, total_new, 0, 0, 0, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
 }
 
@@ -192,7 +192,60 @@ int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int
   const DecodePlan p = plan_decode(*cfg, cache->batch, max_kv_len);
   if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, cache->batch, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
-  const hipError_t e = launch_decode(ctx->c, *cfg, q, max_kv_len, *cache, mode, out, (hipStream_t)stream);
+  const hipError_t e = launch_decode(ctx->c, *cfg, q, max_kv_len, *cache, mode, 0, out, (hipStream_t)stream);
+  return e == hipSuccess ? FLUX_OK : hip_fail(e);
+}
+
+// ---- sparse-decode residency (ring caches)
+
+int flux_kv_append_ring(flux_ctx* ctx, const flux_kv_cache* ring, int n_kv_heads, int head_dim, int n_sink,
+                        int window, const void* k_new, const void* v_new, const int32_t* cu_new, int total_new,
+                        int max_new, void* stream) {
+  if (!ctx || !k_new || !v_new || !cu_new) return FLUX_EINVAL;
+  if (head_dim != 64 && head_dim != 128) return FLUX_EINVAL;
+  if (n_kv_heads <= 0 || total_new < 0 || max_new < 0 || max_new > total_new) return FLUX_EINVAL;
+  if (n_sink < 0 || window < 1) return FLUX_EINVAL;
+  const int rc = check_cache(ring, head_dim);
+  if (rc != FLUX_OK) return rc;
+  if (!aligned16(k_new) || !aligned16(v_new)) return FLUX_EINVAL;
+  if ((long long)n_sink + window > ring->capacity) return FLUX_ECAPACITY;
+  if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
+  if (total_new == 0) return FLUX_OK;
+  const hipError_t e = launch_kv_append(ctx->c, *ring, n_kv_heads, head_dim, k_new, v_new, cu_new, total_new, 1,
+                                        n_sink, window, (hipStream_t)stream);
+  return e == hipSuccess ? FLUX_OK : hip_fail(e);
+}
+
+int flux_kv_compact_ring(flux_ctx* ctx, const flux_kv_cache* src, const flux_kv_cache* dst, int n_kv_heads,
+                         int head_dim, int n_sink, int window, void* stream) {
+  if (!ctx) return FLUX_EINVAL;
+  if (head_dim != 64 && head_dim != 128) return FLUX_EINVAL;
+  if (n_kv_heads <= 0 || n_sink < 0 || window < 1) return FLUX_EINVAL;
+  int rc = check_cache(src, head_dim);
+  if (rc != FLUX_OK) return rc;
+  rc = check_cache(dst, head_dim);
+  if (rc != FLUX_OK) return rc;
+  if (src->batch != dst->batch) return FLUX_EINVAL;
+  if ((long long)n_sink + window > dst->capacity) return FLUX_ECAPACITY;
+  if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
+  const hipError_t e = launch_kv_compact_ring(*src, *dst, n_kv_heads, head_dim, n_sink, window, (hipStream_t)stream);
+  return e == hipSuccess ? FLUX_OK : hip_fail(e);
+}
+
+int flux_attn_decode_ring(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const flux_kv_cache* ring,
+                          void* out, void* stream) {
+  if (!ctx || !q || !out) return FLUX_EINVAL;
+  int rc = check_cfg(cfg);
+  if (rc != FLUX_OK) return rc;
+  rc = check_cache(ring, cfg->head_dim);
+  if (rc != FLUX_OK) return rc;
+  if ((long long)cfg->n_sink + cfg->window > ring->capacity) return FLUX_ECAPACITY;
+  if (!aligned16(q) || !aligned16(out)) return FLUX_EINVAL;
+  const int n_keys = cfg->n_sink + cfg->window;             // the most any sequence attends to
+  const DecodePlan p = plan_decode(*cfg, ring->batch, n_keys);
+  if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, ring->batch, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
+  if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
+  const hipError_t e = launch_decode(ctx->c, *cfg, q, n_keys, *ring, nullptr, 1, out, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
 }
 

@@ -40,7 +40,10 @@ constexpr size_t kHeaderBytes = 4096;         // status + counters
 
 // ---- launchers (each validates nothing: flux_api.hip has done it) ---------------------------
 hipError_t launch_kv_append(const Ctx& c, const flux_kv_cache& cache, int hkv, int d, const void* k_new,
-                            const void* v_new, const int32_t* cu_new, int total_new, hipStream_t s);
+                            const void* v_new, const int32_t* cu_new, int total_new, int ring, int n_sink,
+                            int window, hipStream_t s);
+hipError_t launch_kv_compact_ring(const flux_kv_cache& src, const flux_kv_cache& dst, int hkv, int d, int n_sink,
+                                  int window, hipStream_t s);
 
 struct DecodePlan {
   int chunk;        // keys per workgroup
@@ -49,7 +52,7 @@ struct DecodePlan {
 DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len);
 size_t decode_partials_bytes(const flux_attn_cfg& cfg, int batch, const DecodePlan& p);
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
-                         const flux_kv_cache& cache, const uint8_t* mode, void* out, hipStream_t s);
+                         const flux_kv_cache& cache, const uint8_t* mode, int ring, void* out, hipStream_t s);
 
 hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q, const int32_t* cu_q,
                           int max_q_len, int max_kv_len, const flux_kv_cache& cache, const uint8_t* mode,

@@ -119,3 +119,26 @@ def test_append_and_router_argument_validation(F, nodev):
     assert rc_of(F, F.flux_router, *no_out) == F.FLUX_EINVAL
     huge = list(r_ok); huge[3] = 4096
     assert rc_of(F, F.flux_router, *huge) == F.FLUX_EWORKSPACE
+
+
+def test_ring_argument_validation(F, nodev):
+    good = F.attn_cfg(8, 2, 128, 4, 16)
+    ring = cache_struct(F, capacity=20)                      # exactly n_sink + window rows
+    full = cache_struct(F, capacity=64)
+    ok = (nodev, ring, 2, 128, 4, 16, 4096, 8192, 256, 100, 100)
+    assert rc_of(F, F.flux_kv_append_ring, *ok) == F.FLUX_EHIP                   # any number of rows may be appended
+    assert rc_of(F, F.flux_kv_append_ring, nodev, ring, 2, 128, 4, 17, 4096, 8192, 256, 5, 5) == F.FLUX_ECAPACITY
+    assert rc_of(F, F.flux_kv_append_ring, nodev, ring, 2, 128, -1, 16, 4096, 8192, 256, 5, 5) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_kv_append_ring, nodev, ring, 2, 128, 4, 0, 4096, 8192, 256, 5, 5) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_kv_append_ring, nodev, ring, 2, 128, 4, 16, None, 8192, 256, 5, 5) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_kv_append_ring, nodev, ring, 2, 96, 4, 16, 4096, 8192, 256, 5, 5) == F.FLUX_EINVAL
+
+    assert rc_of(F, F.flux_kv_compact_ring, nodev, full, ring, 2, 128, 4, 16) == F.FLUX_EHIP
+    assert rc_of(F, F.flux_kv_compact_ring, nodev, full, ring, 2, 128, 5, 16) == F.FLUX_ECAPACITY
+    assert rc_of(F, F.flux_kv_compact_ring, nodev, full, cache_struct(F, capacity=20, batch=2), 2, 128, 4, 16) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_kv_compact_ring, nodev, cache_struct(F, k=None), ring, 2, 128, 4, 16) == F.FLUX_EINVAL
+
+    assert rc_of(F, F.flux_attn_decode_ring, nodev, good, 4096, ring, 1024) == F.FLUX_EHIP
+    assert rc_of(F, F.flux_attn_decode_ring, nodev, F.attn_cfg(8, 2, 128, 4, 17), 4096, ring, 1024) == F.FLUX_ECAPACITY
+    assert rc_of(F, F.flux_attn_decode_ring, nodev, good, None, ring, 1024) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_attn_decode_ring, nodev, good, 4100, ring, 1024) == F.FLUX_EINVAL

@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--decode-steps", type=int, default=50)
     ap.add_argument("--decode-warmup", type=int, default=10)
     ap.add_argument("--only", choices=["all", "prefill", "decode", "router"], default="all",

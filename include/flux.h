@@ -49,7 +49,6 @@ enum {
   FLUX_DEV_BAD_LENGTH = 2     /* a kv_len / cu_seqlens value was inconsistent and was clamped */
 };
 
-
 typedef struct flux_ctx flux_ctx;   /* opaque; owns ONLY its device workspace */
 
 /* Attention shape and the SA pattern of one call.
@@ -64,7 +63,8 @@ typedef struct {
 } flux_attn_cfg;
 
 /* One LAYER's KV cache, caller-owned: element (b, h, t, d) of K is
- * k[b*stride_b + h*stride_h + t*stride_t + d], d contiguous, same strides for V. */
+ * k[b*stride_b + h*stride_h + t*stride_t + d], d contiguous, same strides for V.
+ * head_dim <= stride_t <= 2^22 elements. */
 typedef struct {
   void* k;                  /* dev bf16 */
   void* v;                  /* dev bf16 */

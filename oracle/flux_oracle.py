@@ -13,7 +13,8 @@ What it follows (paper sections / equations):
 * Sparse Attention, Eq. (2) of Sec. 2.1: the same softmax over a subset of the
   history.  The subset is the streaming one of Sec. 4.1 / App. C.3: the first
   ``n_sink`` positions plus the ``window`` most recent positions (the query's
-  own position counts as the most recent).
+  own position counts as the most recent).  App. C.3 sets a block size that is
+  "the minimum unit of sparsity": ``block`` > 1 rounds both sets to whole blocks.
 * Grouped-query attention: query head ``h`` reads KV head ``h // (Hq // Hkv)``.
 * Layer Router, Sec. 3.1: prefix/suffix pooling of the first and last ``pool``
   token rows (App. C.1: 100 + 100) into one mean vector, Context Encoder
@@ -54,26 +55,37 @@ def bf16_to_f64(bits) -> np.ndarray:
 
 # --------------------------------------------------------------------------- mask
 
-def visible(i, j, mode: int, n_sink: int, window: int):
+def visible(i, j, mode: int, n_sink: int, window: int, block: int = 1):
     """Whether query position ``i`` attends key position ``j`` (broadcasts).
 
     FA: every ``j <= i``.  SA: ``j <= i`` and (``j`` is one of the first
     ``n_sink`` positions or ``j`` is among the ``window`` most recent, i.e.
     ``i - j < window``).
+
+    ``block`` > 1 is the block-granular form of App. C.3, where a block of
+    ``block`` positions is the minimum unit of sparsity: positions are grouped
+    into blocks of ``block``, the sinks are the first ``ceil(n_sink / block)``
+    blocks, the window is the ``ceil(window / block)`` most recent blocks (the
+    query's own block counts), and a block pair is kept or dropped as a whole,
+    except that the causal order still holds inside the diagonal block.
+    ``block`` = 1 is the token-exact form above.
     """
     i = np.asarray(i)
     j = np.asarray(j)
     causal = j <= i
     if mode == FA:
         return causal
-    return causal & ((j < n_sink) | (i - j < window))
+    bi, bj = i // block, j // block
+    sink_blocks = -(-n_sink // block)
+    window_blocks = -(-window // block)
+    return causal & ((bj < sink_blocks) | (bi - bj < window_blocks))
 
 
-def mask_matrix(n_q: int, n_kv: int, mode: int, n_sink: int, window: int) -> np.ndarray:
+def mask_matrix(n_q: int, n_kv: int, mode: int, n_sink: int, window: int, block: int = 1) -> np.ndarray:
     """Explicit boolean mask [n_q, n_kv]; row r is query position ``n_kv - n_q + r``."""
     i = (n_kv - n_q + np.arange(n_q))[:, None]
     j = np.arange(n_kv)[None, :]
-    return visible(i, j, mode, n_sink, window)
+    return visible(i, j, mode, n_sink, window, block)
 
 
 # --------------------------------------------------------------------------- attention
@@ -87,7 +99,7 @@ def softmax_rows(s: np.ndarray, mask: np.ndarray) -> np.ndarray:
 
 
 def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mode: int, n_sink: int, window: int,
-              scale: float | None = None, return_probs: bool = False):
+              scale: float | None = None, return_probs: bool = False, block: int = 1):
     """One sequence, one layer, explicit mask matrix.
 
     q [n_q, Hq, D], k and v [n_kv, Hkv, D] (fp64).  Returns out [n_q, Hq, D]
@@ -99,7 +111,7 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mode: int, n_sink: in
     g = hq // hkv
     if scale is None:
         scale = 1.0 / np.sqrt(d)
-    mask = mask_matrix(n_q, n_kv, mode, n_sink, window)
+    mask = mask_matrix(n_q, n_kv, mode, n_sink, window, block)
     out = np.empty((n_q, hq, d), dtype=np.float64)
     probs = np.empty((hq, n_q, n_kv), dtype=np.float64) if return_probs else None
     for h in range(hq):
@@ -114,7 +126,7 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mode: int, n_sink: in
 
 
 def attention_row(q_row: np.ndarray, k: np.ndarray, v: np.ndarray, i: int, mode: int, n_sink: int,
-                  window: int, scale: float | None = None) -> np.ndarray:
+                  window: int, scale: float | None = None, block: int = 1) -> np.ndarray:
     """One query position ``i`` of one KV-head group, predicate evaluated along the row.
 
     q_row [G, D] (the G query heads sharing this KV head), k and v [>= i+1, D].
@@ -125,7 +137,7 @@ def attention_row(q_row: np.ndarray, k: np.ndarray, v: np.ndarray, i: int, mode:
     if scale is None:
         scale = 1.0 / np.sqrt(d)
     j = np.arange(i + 1)
-    keep = visible(i, j, mode, n_sink, window)
+    keep = visible(i, j, mode, n_sink, window, block)
     kk = k[: i + 1][keep]
     vv = v[: i + 1][keep]
     s = scale * (q_row @ kk.T)                        # [G, n_visible]
@@ -150,7 +162,7 @@ class KVCache:
         return self.k[b].shape[0]
 
 
-def prefill(cache: KVCache, q_list, k_list, v_list, modes, n_sink: int, window: int, scale=None):
+def prefill(cache: KVCache, q_list, k_list, v_list, modes, n_sink: int, window: int, scale=None, block: int = 1):
     """Append each sequence's new K/V rows, then attend with its new queries (Sec. 3.3).
 
     ``modes[b]`` is that sequence's cached decision for this layer.
@@ -158,17 +170,17 @@ def prefill(cache: KVCache, q_list, k_list, v_list, modes, n_sink: int, window: 
     outs = []
     for b, (q, k, v) in enumerate(zip(q_list, k_list, v_list)):
         cache.append(b, k, v)
-        outs.append(attention(q, cache.k[b], cache.v[b], int(modes[b]), n_sink, window, scale))
+        outs.append(attention(q, cache.k[b], cache.v[b], int(modes[b]), n_sink, window, scale, block=block))
     return outs
 
 
 def decode_step(cache: KVCache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, modes,
-                n_sink: int, window: int, scale=None) -> np.ndarray:
+                n_sink: int, window: int, scale=None, block: int = 1) -> np.ndarray:
     """One autoregressive step: q [B, Hq, D], k_new/v_new [B, Hkv, D] -> out [B, Hq, D]."""
     out = np.empty_like(q)
     for b in range(q.shape[0]):
         cache.append(b, k_new[b][None], v_new[b][None])
-        out[b] = attention(q[b][None], cache.k[b], cache.v[b], int(modes[b]), n_sink, window, scale)[0]
+        out[b] = attention(q[b][None], cache.k[b], cache.v[b], int(modes[b]), n_sink, window, scale, block=block)[0]
     return out
 
 

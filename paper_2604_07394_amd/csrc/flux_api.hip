@@ -43,6 +43,7 @@ int check_cache(const flux_kv_cache* kc, int head_dim) {
   if (!aligned16(kc->k) || !aligned16(kc->v)) return FLUX_EINVAL;
   if (kc->stride_t < head_dim || kc->stride_h < 0 || kc->stride_b < 0) return FLUX_EINVAL;
   if ((kc->stride_t | kc->stride_h | kc->stride_b) & 7) return FLUX_EINVAL;
+  if (kc->stride_t > (1 << 22)) return FLUX_EINVAL;        // 32-bit byte offsets inside a 64-row tile
   return FLUX_OK;
 }
 

@@ -88,6 +88,7 @@ def test_attention_argument_validation(F, nodev):
     assert rc_of(F, F.flux_attn_prefill, *args(mk=65)) == F.FLUX_ECAPACITY
     assert rc_of(F, F.flux_attn_prefill, *args(cache=cache_struct(F, stride_t=64))) == F.FLUX_EINVAL    # stride < D
     assert rc_of(F, F.flux_attn_prefill, *args(cache=cache_struct(F, stride_t=132))) == F.FLUX_EINVAL   # 16-byte rule
+    assert rc_of(F, F.flux_attn_prefill, *args(cache=cache_struct(F, stride_t=(1 << 22) + 8))) == F.FLUX_EINVAL
     assert rc_of(F, F.flux_attn_prefill, *args(cache=cache_struct(F, k=None))) == F.FLUX_EINVAL
     assert rc_of(F, F.flux_attn_prefill, None, good, 4096, 768, 8, 32, kc, 512, 1024) == F.FLUX_EINVAL  # no context
 

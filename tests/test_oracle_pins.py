@@ -342,3 +342,66 @@ def test_ring_compaction_equals_row_by_row_appends_and_bulk_append():
     for other in (b_, c):
         assert np.array_equal(a.pos[0], other.pos[0]) and np.array_equal(a.k[0], other.k[0]) and np.array_equal(a.v[0], other.v[0])
     assert a.pos[0].tolist() == [0, 1, 14, 15, 16, 13]      # rows 2..5 hold the p with (p - 2) % 4 = 0..3
+
+
+# ----------------------------------------------------------------------------- block-granular mask (App. C.3)
+
+def test_block_one_is_the_token_exact_mask():
+    for n_sink, window in [(3, 5), (0, 7), (16, 16)]:
+        assert np.array_equal(O.mask_matrix(50, 50, SA, n_sink, window, block=1), O.mask_matrix(50, 50, SA, n_sink, window))
+
+
+@pytest.mark.parametrize("n,n_sink,window,block", [(96, 8, 16, 8), (100, 5, 20, 8), (70, 0, 9, 4), (128, 128, 64, 64), (40, 3, 1, 4)])
+def test_block_is_the_minimum_unit_of_sparsity(n, n_sink, window, block):
+    """Off the diagonal every block x block tile of the mask is all-kept or all-dropped; the diagonal tile is
+    the causal triangle; the kept block columns of block row R are the first ceil(n_sink / block) and the
+    ceil(window / block) most recent, counted without overlap (closed form); written without O.visible."""
+    m = O.mask_matrix(n, n, SA, n_sink, window, block)
+    sb, wb = math.ceil(n_sink / block), math.ceil(window / block)
+    for R in range(math.ceil(n / block)):
+        rows = slice(R * block, min((R + 1) * block, n))
+        kept = 0
+        for Cb in range(R + 1):
+            cols = slice(Cb * block, min((Cb + 1) * block, n))
+            tile = m[rows, cols]
+            if Cb == R:
+                assert np.array_equal(tile, np.tril(np.ones(tile.shape, dtype=bool)))
+                kept += 1
+            else:
+                assert tile.all() or not tile.any()
+                assert tile.all() == (Cb < sb or R - Cb < wb)
+                kept += int(tile.all())
+        assert kept == min(R + 1, wb) + max(0, min(sb, R + 1 - wb))
+        assert not m[rows, (R + 1) * block:].any()                      # nothing from the future
+
+
+def test_block_granular_attention_matches_brute_force():
+    """Pure-Python enumeration of (i, j) pairs with the block rule spelled out from scratch."""
+    g = rng(40)
+    n, d, n_sink, window, block = 23, 4, 3, 6, 4
+    q, k, v = g.standard_normal((n, 2, d)), g.standard_normal((n, 1, d)), g.standard_normal((n, 1, d))
+    out = O.attention(q, k, v, SA, n_sink, window, block=block)
+    sink_blocks, window_blocks = 1, 2                                     # ceil(3 / 4), ceil(6 / 4)
+    for i in range(n):
+        for h in range(2):
+            num, den = np.zeros(d), 0.0
+            for j in range(i + 1):
+                if j // block < sink_blocks or i // block - j // block < window_blocks:
+                    w = math.exp(float(q[i, h] @ k[j, 0]) / math.sqrt(d))
+                    num += w * v[j, 0]
+                    den += w
+            assert np.allclose(out[i, h], num / den, rtol=0, atol=1e-12)
+    # the row form agrees with the matrix form
+    for i in (0, 3, 4, 11, 22):
+        assert np.allclose(O.attention_row(q[i], k[:, 0], v[:, 0], i, SA, n_sink, window, block=block), out[i], rtol=0, atol=1e-13)
+
+
+def test_block_granular_decode_equals_last_prefill_row():
+    g = rng(41)
+    n, n_sink, window, block = 37, 5, 9, 4
+    q, k, v = g.standard_normal((n, 4, 8)), g.standard_normal((n, 2, 8)), g.standard_normal((n, 2, 8))
+    whole = O.attention(q, k, v, SA, n_sink, window, block=block)
+    cache = O.KVCache(1, 2, 8)
+    cache.append(0, k[:-1], v[:-1])
+    step = O.decode_step(cache, q[-1][None], k[-1][None], v[-1][None], [SA], n_sink, window, block=block)
+    assert np.allclose(step[0], whole[-1], rtol=0, atol=1e-13)

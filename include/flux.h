@@ -60,6 +60,11 @@ typedef struct {
   int32_t n_sink, window;
   float softmax_scale;      /* 0 => 1/sqrt(head_dim) (the scale Eq. 1 leaves out "for clarity") */
   int32_t out_dtype;        /* 0 = bf16, 1 = fp32 */
+  int32_t sa_block;         /* 0 or 1: the token-exact SA rule above.  A power of two b > 1: the
+                               block-granular rule of App. C.3 (a block of b positions is the minimum
+                               unit of sparsity; the paper uses 64): with B(x) = x / b, key j is seen
+                               by query i iff j <= i and (B(j) < ceil(n_sink / b) or
+                               B(i) - B(j) < ceil(window / b)). */
 } flux_attn_cfg;
 
 /* One LAYER's KV cache, caller-owned: element (b, h, t, d) of K is
@@ -136,8 +141,8 @@ int flux_attn_prefill(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, co
  * [kv_len[b]-window, kv_len[b]) and never touches the rest (App. B.3).
  * max_kv_len: host upper bound on the number of keys any sequence of this call ATTENDS TO; the
  * largest kv_len[b] is always valid.  A caller that has read the cached mask back once and knows
- * every sequence of this layer is SA may pass min(max kv_len, n_sink + window), which sizes the
- * launch for the sparse case. */
+ * every sequence of this layer is SA may pass min(max kv_len, n_sink + window) (both rounded up to
+ * multiples of sa_block when that is set), which sizes the launch for the sparse case. */
 int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int max_kv_len,
                      const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream);
 
@@ -168,7 +173,8 @@ int flux_kv_compact_ring(flux_ctx* ctx, const flux_kv_cache* src, const flux_kv_
 
 /* flux_attn_decode of a sparse layer on its ring cache: the query of sequence b sits at position
  * kv_len[b] - 1 (append first) and attends to every stored row (Eq. 2).  No mode argument: a ring cache
- * holds a sparse layer.  cfg->n_sink and cfg->window are the ring geometry. */
+ * holds a sparse layer.  cfg->n_sink and cfg->window are the ring geometry; with cfg->sa_block = b > 1 the
+ * ring must have been filled with n_sink and window rounded up to multiples of b. */
 int flux_attn_decode_ring(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const flux_kv_cache* ring,
                           void* out, void* stream);
 

@@ -32,7 +32,7 @@ EXPORTS = ["flux_create", "flux_destroy", "flux_strerror", "flux_workspace_neede
 class FluxAttnCfg(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("n_sink", C.c_int32), ("window", C.c_int32), ("softmax_scale", C.c_float),
-                ("out_dtype", C.c_int32)]
+                ("out_dtype", C.c_int32), ("sa_block", C.c_int32)]
 
 
 class FluxKVCache(C.Structure):
@@ -116,8 +116,8 @@ def flux_destroy(ctx: int) -> None:
     _check(_lib.flux_destroy(ctx))
 
 
-def attn_cfg(n_q_heads, n_kv_heads, head_dim, n_sink, window, softmax_scale=0.0, out_dtype=0) -> FluxAttnCfg:
-    return FluxAttnCfg(n_q_heads, n_kv_heads, head_dim, n_sink, window, softmax_scale, out_dtype)
+def attn_cfg(n_q_heads, n_kv_heads, head_dim, n_sink, window, softmax_scale=0.0, out_dtype=0, sa_block=0) -> FluxAttnCfg:
+    return FluxAttnCfg(n_q_heads, n_kv_heads, head_dim, n_sink, window, softmax_scale, out_dtype, sa_block)
 
 
 def flux_workspace_needed(cfg: FluxAttnCfg, batch: int, max_kv_len: int) -> int:

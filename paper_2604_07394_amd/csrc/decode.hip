@@ -34,17 +34,22 @@ struct DecodeArgs {
   int capacity;
   int hq, hkv, group;     // group = hq / hkv
   int qblocks;            // ceil(group / 16)
-  int n_sink, window;
+  int sink_lim, win_blocks, blk_shift;   // SA geometry (see sa_geom)
   int chunk, n_chunks;
   int ring;               // != 0: the cache is a sink + ring store of a sparse layer, kv_len is logical, no mode bytes
   float scale_log2;       // softmax scale * log2(e)
   float* partials;        // [B, Hq, n_chunks, D + 2]
 };
 
-// number of keys sequence b attends to, and whether the sparse list (sinks + tail) applies
-__device__ __forceinline__ int visible_len(int n, int md, int n_sink, int window, bool& sparse) {
-  sparse = (md == 0) && (n > n_sink + window);
-  return sparse ? n_sink + window : n;
+// Number of keys the query at position n - 1 attends to.  The visible list is the sinks [0, s_end)
+// followed by the window tail [tail_start, n); `sparse` says whether anything lies hidden between them.
+__device__ __forceinline__ int visible_len(int n, int md, int sink_lim, int win_blocks, int shift, bool& sparse,
+                                           int& s_end, int& tail_start) {
+  s_end = n < sink_lim ? n : sink_lim;
+  const int lo = n > 0 ? window_start(n - 1, shift, win_blocks) : 0;
+  tail_start = lo > s_end ? lo : s_end;
+  sparse = (md == 0) && (tail_start > s_end);
+  return sparse ? s_end + (n - tail_start) : n;
 }
 
 template <int D>
@@ -69,13 +74,16 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   int len = a.kv_len[b];
   len = len < 0 ? 0 : ((!a.ring && len > a.capacity) ? a.capacity : len);
   bool sparse;
-  const int n_vis = visible_len(len, a.ring ? 0 : a.mode[b], a.n_sink, a.window, sparse);
+  int s_end, tail_start;
+  const int n_vis = visible_len(len, a.ring ? 0 : a.mode[b], a.sink_lim, a.win_blocks, a.blk_shift, sparse, s_end, tail_start);
   const int c0 = ci * a.chunk;
   if (c0 >= n_vis) return;                                  // uniform for the whole workgroup
   const int c1 = min(c0 + a.chunk, n_vis);
-  const int tail0 = len - a.window - a.n_sink;              // list index p >= n_sink maps to key p + tail0
-  // ring store: that key sits in row n_sink + (p + tail0 - n_sink) % window = n_sink + (p - n_sink + ring0) % window
-  const int ring0 = (a.ring && sparse) ? tail0 % a.window : 0;
+  const int tail0 = tail_start - s_end;                     // list index p >= s_end maps to key p + tail0
+  // ring store (s_end = sink_lim when sparse): that key sits in row sink_lim + (p + tail0 - sink_lim) % ring_window
+  //                                                               = sink_lim + (p - sink_lim + ring0) % ring_window
+  const int ring_window = a.win_blocks << a.blk_shift;
+  const int ring0 = (a.ring && sparse) ? tail0 % ring_window : 0;
 
   const __bf16* kbase = a.k + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
   const __bf16* vbase = a.v + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
@@ -95,10 +103,10 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
 
   auto key_of = [&](int p) -> int64_t {
     p = p < c1 ? p : c1 - 1;                                // keep every address inside the chunk
-    if (!sparse || p < a.n_sink) return (int64_t)p;
+    if (!sparse || p < s_end) return (int64_t)p;
     if (!a.ring) return (int64_t)p + tail0;
-    const int x = p - a.n_sink + ring0;                     // < 2 * window
-    return (int64_t)a.n_sink + (x >= a.window ? x - a.window : x);
+    const int x = p - s_end + ring0;                        // < 2 * ring_window
+    return (int64_t)s_end + (x >= ring_window ? x - ring_window : x);
   };
 
   u32x4 kreg[2][KC], vreg[VL];
@@ -243,7 +251,7 @@ struct CombineArgs {
   const float* partials;
   const int32_t* kv_len;
   const uint8_t* mode;
-  int capacity, hq, n_sink, window, chunk, n_chunks, out_fp32, ring;
+  int capacity, hq, sink_lim, win_blocks, blk_shift, chunk, n_chunks, out_fp32, ring;
   float scale_log2;
   void* out;
 };
@@ -257,7 +265,8 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
   int len = a.kv_len[b];
   len = len < 0 ? 0 : ((!a.ring && len > a.capacity) ? a.capacity : len);
   bool sparse;
-  const int n_vis = visible_len(len, a.ring ? 0 : a.mode[b], a.n_sink, a.window, sparse);
+  int s_end, tail_start;
+  const int n_vis = visible_len(len, a.ring ? 0 : a.mode[b], a.sink_lim, a.win_blocks, a.blk_shift, sparse, s_end, tail_start);
   const int nc = min((n_vis + a.chunk - 1) / a.chunk, a.n_chunks);   // chunks the launch covered
   const float* base = a.partials + ((int64_t)b * a.hq + head) * a.n_chunks * RED;
   // ---- maximum over the chunks (threads take chunks round-robin, then a block reduction)
@@ -332,8 +341,10 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   a.hkv = cfg.n_kv_heads;
   a.group = cfg.n_q_heads / cfg.n_kv_heads;
   a.qblocks = (a.group + 15) / 16;
-  a.n_sink = cfg.n_sink;
-  a.window = cfg.window;
+  const SaGeom geom = sa_geom(cfg);
+  a.sink_lim = geom.sink_lim;
+  a.win_blocks = geom.win_blocks;
+  a.blk_shift = geom.shift;
   a.chunk = plan.chunk;
   a.n_chunks = plan.n_chunks;
   a.ring = ring;
@@ -351,8 +362,9 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   ca.mode = mode;
   ca.capacity = cache.capacity;
   ca.hq = cfg.n_q_heads;
-  ca.n_sink = cfg.n_sink;
-  ca.window = cfg.window;
+  ca.sink_lim = geom.sink_lim;
+  ca.win_blocks = geom.win_blocks;
+  ca.blk_shift = geom.shift;
   ca.chunk = plan.chunk;
   ca.n_chunks = plan.n_chunks;
   ca.out_fp32 = cfg.out_dtype;

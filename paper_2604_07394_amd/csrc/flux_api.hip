@@ -34,6 +34,7 @@ int check_cfg(const flux_attn_cfg* cfg) {
   if (cfg->n_sink < 0 || cfg->window < 1) return FLUX_EINVAL;   // the query's own key must stay visible
   if (!(cfg->softmax_scale >= 0.f) || isinf(cfg->softmax_scale)) return FLUX_EINVAL;
   if (cfg->out_dtype != 0 && cfg->out_dtype != 1) return FLUX_EINVAL;
+  if (cfg->sa_block < 0 || cfg->sa_block > 65536 || (cfg->sa_block & (cfg->sa_block - 1))) return FLUX_EINVAL;
   return FLUX_OK;
 }
 
@@ -240,9 +241,11 @@ int flux_attn_decode_ring(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q
   if (rc != FLUX_OK) return rc;
   rc = check_cache(ring, cfg->head_dim);
   if (rc != FLUX_OK) return rc;
-  if ((long long)cfg->n_sink + cfg->window > ring->capacity) return FLUX_ECAPACITY;
+  const SaGeom geom = sa_geom(*cfg);
+  const long long ring_rows = (long long)geom.sink_lim + ((long long)geom.win_blocks << geom.shift);
+  if (ring_rows > ring->capacity) return FLUX_ECAPACITY;
   if (!aligned16(q) || !aligned16(out)) return FLUX_EINVAL;
-  const int n_keys = cfg->n_sink + cfg->window;             // the most any sequence attends to
+  const int n_keys = (int)ring_rows;                         // the most any sequence attends to
   const DecodePlan p = plan_decode(*cfg, ring->batch, n_keys);
   if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, ring->batch, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);

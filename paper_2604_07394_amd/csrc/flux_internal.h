@@ -34,6 +34,26 @@ struct Ctx {
   size_t partials_bytes;
 };
 
+// The SA visible set in block units (App. C.3): positions are grouped into blocks of 2^shift; the sinks
+// are the positions below sink_lim (whole blocks), the window of query position i starts at
+// window_start(i).  shift = 0 is the token-exact rule: sink_lim = n_sink, window_start(i) = i - window + 1.
+struct SaGeom {
+  int shift, sink_lim, win_blocks;
+};
+inline SaGeom sa_geom(const flux_attn_cfg& cfg) {
+  int b = cfg.sa_block > 1 ? cfg.sa_block : 1, sh = 0;
+  while ((1 << sh) < b) ++sh;
+  SaGeom g;
+  g.shift = sh;
+  g.sink_lim = ((cfg.n_sink + b - 1) >> sh) << sh;
+  g.win_blocks = (cfg.window + b - 1) >> sh;
+  return g;
+}
+__device__ __forceinline__ int window_start(int i, int shift, int win_blocks) {
+  const int lo = ((i >> shift) - win_blocks + 1) << shift;
+  return lo > 0 ? lo : 0;
+}
+
 constexpr int kCounters = 64;
 constexpr size_t kSmallBytes = 8u << 20;      // router: batch * (splits * hidden + inner) floats
 constexpr size_t kHeaderBytes = 4096;         // status + counters

@@ -27,7 +27,7 @@ struct PrefillArgs {
   int capacity;
   int hq, hkv, group, batch;
   int xcd_map;            // 0 plain, 1 pairs-per-XCD, 2 XCDs-per-pair (see the kernel)
-  int n_sink, window;
+  int sink_lim, win_blocks, blk_shift;   // SA geometry (see sa_geom)
   int n_qtiles;
   float scale_log2;
   int out_fp32;
@@ -120,6 +120,10 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   const bool wave_active = r_w0 < n_q;
   const int r_mine = min(r_w0 + n, n_q - 1);                 // clamped row of this lane's query
   const int i_mine = pos0 + r_w0 + n;                        // its position (unclamped)
+  // first key of the SA window of this lane's row, of the wave's first row and of its last row
+  const int w_lo_mine = window_start(i_mine, a.blk_shift, a.win_blocks);
+  const int w_lo_first = window_start(i_w_min, a.blk_shift, a.win_blocks);
+  const int w_lo_last = window_start(max(i_w_max, i_w_min), a.blk_shift, a.win_blocks);
 
   // ---- Q operand: lane (n, g) holds d = 16*kc + 8*g .. +7 of its query row
   bf16x8 qf[KC];
@@ -135,9 +139,9 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   if (!sa) {
     n_a = last_blk + 1; win0 = 0; n_b = 0;
   } else {
-    const int sink_end = min(a.n_sink, i_tile_max + 1);      // keys [0, sink_end) are sinks in reach
+    const int sink_end = min(a.sink_lim, i_tile_max + 1);    // keys [0, sink_end) are sinks in reach
     n_a = (sink_end + BN - 1) / BN;
-    const int wfirst = max(i_tile_min - a.window + 1, 0);    // first key any row's window reaches
+    const int wfirst = window_start(i_tile_min, a.blk_shift, a.win_blocks);   // first key any row's window reaches
     win0 = max(wfirst / BN, n_a);
     n_b = last_blk + 1 - win0;
     if (n_b < 0) n_b = 0;
@@ -222,10 +226,10 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
     bool skip = !wave_active || j0 > i_w_max;
     bool need_mask = j0 + BN - 1 > i_w_min;
     if (sa) {
-      const bool all_sink = j0 + BN <= a.n_sink;
+      const bool all_sink = j0 + BN <= a.sink_lim;
       if (!all_sink) {
-        if (j0 >= a.n_sink && j0 + BN - 1 < i_w_min - a.window + 1) skip = true;   // before every window
-        if (i_w_max - j0 >= a.window) need_mask = true;                           // a window edge falls inside
+        if (j0 >= a.sink_lim && j0 + BN - 1 < w_lo_first) skip = true;            // before every window
+        if (j0 < w_lo_last) need_mask = true;                                     // a window edge falls inside
       }
     }
     if (skip) continue;
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
-          const bool vis = (j <= i_mine) & (!sa | (j < a.n_sink) | (i_mine - j < a.window));
+          const bool vis = (j <= i_mine) & (!sa | (j < a.sink_lim) | (j >= w_lo_mine));
           s[kb][r] = vis ? s[kb][r] : -INFINITY;
         }
     }
@@ -346,8 +350,10 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.hkv = cfg.n_kv_heads;
   a.group = cfg.n_q_heads / cfg.n_kv_heads;
   a.batch = cache.batch;
-  a.n_sink = cfg.n_sink;
-  a.window = cfg.window;
+  const SaGeom geom = sa_geom(cfg);
+  a.sink_lim = geom.sink_lim;
+  a.win_blocks = geom.win_blocks;
+  a.blk_shift = geom.shift;
   a.n_qtiles = (max_q_len + BM - 1) / BM;
   (void)c;
   const int nkb = 2;                                          // 64 keys per iteration

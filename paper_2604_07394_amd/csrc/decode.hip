@@ -333,12 +333,12 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
 
 DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len) {
   // Aim for about 1024 workgroups (4 per CU, two rounds of the two that fit a CU) with chunks of at
-  // least 512 keys (128 per wave), so that the per-chunk merge stays a small fraction of the streaming.
+  // least 256 keys (64 per wave), so that the per-chunk merge stays a small fraction of the streaming.
   const long long pairs = (long long)batch * cfg.n_kv_heads * ((cfg.n_q_heads / cfg.n_kv_heads + 15) / 16);
   long long total = pairs * (long long)(max_kv_len > 0 ? max_kv_len : 1);
   long long chunk = (total + 1023) / 1024;
   chunk = ((chunk + 127) / 128) * 128;
-  if (chunk < 512) chunk = 512;
+  if (chunk < 256) chunk = 256;
   DecodePlan p;
   p.chunk = (int)chunk;
   p.n_chunks = (int)(((long long)(max_kv_len > 0 ? max_kv_len : 1) + chunk - 1) / chunk);

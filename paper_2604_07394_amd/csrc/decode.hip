@@ -39,6 +39,7 @@ struct DecodeArgs {
   int ring;               // != 0: the cache is a sink + ring store of a sparse layer, kv_len is logical, no mode bytes
   float scale_log2;       // softmax scale * log2(e)
   float* partials;        // [B, Hq, n_chunks, D + 2]
+  uint32_t* status;       // sticky device status word
 };
 
 // Number of keys the query at position n - 1 attends to.  The visible list is the sinks [0, s_end)
@@ -72,6 +73,9 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   const int b = blockIdx.z;
 
   int len = a.kv_len[b];
+  // a length the host could not see (negative, or past the capacity of a full cache) is clamped and reported
+  if (ci == 0 && blockIdx.y == 0 && tid == 0 && (len < 0 || (!a.ring && len > a.capacity)))
+    atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
   len = len < 0 ? 0 : ((!a.ring && len > a.capacity) ? a.capacity : len);
   bool sparse;
   int s_end, tail_start;
@@ -376,6 +380,7 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   a.ring = ring;
   a.scale_log2 = scale * kLog2e;
   a.partials = c.partials;
+  a.status = c.status;
   const dim3 grid(plan.n_chunks, cfg.n_kv_heads * a.qblocks, cache.batch);
   // K and V bytes one call may read, against the 256 MB last-level cache
   const bool nt = 4.0 * cache.batch * cfg.n_kv_heads * cfg.head_dim * (double)max_kv_len > 256.0 * 1024 * 1024;

@@ -32,6 +32,7 @@ struct PrefillArgs {
   float scale_log2;
   int out_fp32;
   void* out;
+  uint32_t* status;       // sticky device status word
 };
 
 constexpr int BM = 128;   // query rows per workgroup
@@ -102,11 +103,18 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   const int kvh = h / a.group;
 
   const int q_begin = a.cu_q[b];
-  const int n_q = a.cu_q[b + 1] - q_begin;
-  if (qt * BM >= n_q) return;                                // uniform for the workgroup
+  const int n_q_given = a.cu_q[b + 1] - q_begin;
   int len = a.kv_len[b];
+  // lengths the host could not see: negative, past the capacity, or more queries than cached positions;
+  // they are clamped below, and reported once per sequence
+  if (qt == a.n_qtiles - 1 && h == 0 && tid == 0 && (n_q_given < 0 || len < 0 || len > a.capacity || n_q_given > len))
+    atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
   len = len > a.capacity ? a.capacity : len;
   if (len < 1) return;                                       // nothing cached: nothing to attend
+  // the queries are the last n_q cached positions, so there cannot be more of them than positions: the
+  // surplus rows of an inconsistent call are not computed (every key tile then starts inside the cache)
+  const int n_q = n_q_given < len ? n_q_given : len;
+  if (qt * BM >= n_q) return;                                // uniform for the workgroup
   const int pos0 = max(len - n_q, 0);                        // position of query row 0
   const bool sa = a.mode[b] == 0;
 
@@ -355,11 +363,11 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.win_blocks = geom.win_blocks;
   a.blk_shift = geom.shift;
   a.n_qtiles = (max_q_len + BM - 1) / BM;
-  (void)c;
   const int nkb = 2;                                          // 64 keys per iteration
   a.scale_log2 = scale * kLog2e;
   a.out_fp32 = cfg.out_dtype;
   a.out = out;
+  a.status = c.status;
   if (a.n_qtiles == 0) return hipSuccess;
   const long long n_pairs = (long long)cache.batch * cfg.n_kv_heads;
   long long n_wg;

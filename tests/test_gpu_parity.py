@@ -453,3 +453,32 @@ def test_decode_with_an_empty_cache_row_returns_zeros(F, ctx):
     ref = O.attention(O.bf16_to_f64(qb[0])[None], lay.ocache.k[0], lay.ocache.v[0], SA, 8, 64)[0]
     H.assert_close(out[0].cpu().numpy(), ref, "non-empty sequence next to an empty one")
     assert torch.equal(out[1], torch.zeros_like(out[1]))
+
+
+def test_inconsistent_lengths_are_clamped_and_flagged(F, ctx):
+    """kv_len values the host cannot see: past the capacity in decode, fewer cached positions than queries
+    in prefill.  Nothing leaves the buffers, the sticky status word reports FLUX_DEV_BAD_LENGTH once read."""
+    lay = Layer(F, ctx, 63, 1, 8, 2, 128, 256, 8, 64)
+    qb, kb, vb = lay.new_tokens([256])
+    lay.append(kb, vb, [256])
+    assert F.flux_last_device_status(ctx) == 0
+    q1 = qb[255].reshape(1, 8, 128)
+    good, ref = lay.decode(q1, [FA])
+    H.assert_close(good, ref, "decode at capacity")
+    lay.cache.kv_len.fill_(256 + 5)                                   # corrupt: beyond the buffers
+    out = torch.full((1, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+    F.flux_attn_decode(ctx, lay.cfg, H.bits_to_torch(q1), 256, lay.cache, u8([FA]), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), good)                    # clamped to the capacity
+    assert F.flux_last_device_status(ctx) & F.FLUX_DEV_BAD_LENGTH
+    assert F.flux_last_device_status(ctx) == 0                        # reading clears it
+    lay.cache.kv_len.fill_(50)                                        # fewer cached positions than queries
+    outp = torch.full((100, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+    F.flux_attn_prefill(ctx, lay.cfg, H.bits_to_torch(qb[:100]), cu([100]), 100, 256, lay.cache, u8([SA]), outp)
+    torch.cuda.synchronize()
+    # only as many query rows as there are cached positions are computed (as the last 50 positions of a
+    # 50-token cache); the surplus rows are left alone
+    ref = O.attention(O.bf16_to_f64(qb[:50]), lay.ocache.k[0][:50], lay.ocache.v[0][:50], SA, 8, 64)
+    H.assert_close(outp[:50].cpu().numpy(), ref, "prefill with more queries than cached positions")
+    assert torch.isnan(outp[50:]).all()
+    assert F.flux_last_device_status(ctx) & F.FLUX_DEV_BAD_LENGTH

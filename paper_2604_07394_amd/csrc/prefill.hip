@@ -363,7 +363,6 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.win_blocks = geom.win_blocks;
   a.blk_shift = geom.shift;
   a.n_qtiles = (max_q_len + BM - 1) / BM;
-  const int nkb = 2;                                          // 64 keys per iteration
   a.scale_log2 = scale * kLog2e;
   a.out_fp32 = cfg.out_dtype;
   a.out = out;
@@ -384,13 +383,9 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   }
   if (n_wg > 0x7FFFFFFFll) return hipErrorInvalidValue;
   const dim3 grid((unsigned)n_wg);
-  if (cfg.head_dim == 128) {
-    if (nkb == 1) hipLaunchKernelGGL((prefill_kernel<128, 1>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(256), 0, s, a);
-  } else {
-    if (nkb == 1) hipLaunchKernelGGL((prefill_kernel<64, 1>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((prefill_kernel<64, 2>), grid, dim3(256), 0, s, a);
-  }
+  // 64 keys per iteration (NKB = 2): 32-key tiles with three workgroups per CU measured no faster
+  if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((prefill_kernel<64, 2>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

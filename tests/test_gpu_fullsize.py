@@ -161,6 +161,32 @@ def test_long_context_decode_shape_one_layer(F, G, ctx):
             print("long decode", b, kvh, mode, "max-abs %.2e rel-L2 %.2e" % e)
     assert F.flux_last_device_status(ctx) == 0
 
+    # ---- the same layer in the sparse-decode residency bench.py times: compact the 131073-token cache to a
+    # ring of 128 + 4096 rows, append the next token to both, decode on the ring.  Bit-equal to the SA decode
+    # on the full cache, and within tolerance of the oracle on sampled (sequence, KV head) pairs.
+    ring = F.KVCache.empty(B, HKV, NS + W, D)
+    F.flux_kv_compact_ring(ctx, cache, ring, HKV, D, NS, W)
+    G.fill_normal_bf16(kd, SEED, synth.stream_id(synth.STREAM_KDEC, 0, 1))
+    G.fill_normal_bf16(vd, SEED, synth.stream_id(synth.STREAM_VDEC, 0, 1))
+    G.fill_normal_bf16(qd, SEED, synth.stream_id(synth.STREAM_QDEC, 0, 1))
+    one = i32(list(range(B + 1)))
+    F.flux_kv_append(ctx, cache, HKV, D, kd[0, 0], vd[0, 0], one, B, 1)
+    F.flux_kv_append_ring(ctx, ring, HKV, D, NS, W, kd[0, 0], vd[0, 0], one, B, 1)
+    o_ring = torch.full((B, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
+    o_full = torch.full((B, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
+    F.flux_attn_decode_ring(ctx, cfg, qd[0, 0], ring, o_ring)
+    F.flux_attn_decode(ctx, cfg, qd[0, 0], NS + W, cache, u8([SA] * B), o_full)
+    torch.cuda.synchronize()
+    assert ring.kv_len.cpu().tolist() == [N + 2] * B
+    assert torch.equal(o_ring, o_full)
+    q = qd[0, 0].view(B, HQ, D)
+    for b, kvh in ((1, 4), (6, 0)):
+        kf = H.torch_to_f64(kc[b, kvh, :N + 2])
+        vf = H.torch_to_f64(vc[b, kvh, :N + 2])
+        ref = O.attention_row(H.torch_to_f64(q[b, kvh * g:(kvh + 1) * g]), kf, vf, N + 1, SA, NS, W)
+        H.assert_close(H.torch_to_f64(o_ring[b, kvh * g:(kvh + 1) * g]), ref, f"ring decode at full size, seq {b} kv head {kvh}")
+    assert F.flux_last_device_status(ctx) == 0
+
 
 def test_high_sparsity_prefill_shape(F, G, ctx):
     """High-sparsity prefill workload, one SA and one FA layer: batch 2, 65536 tokens, 28/4 heads (group

@@ -386,7 +386,31 @@ def main():
 
     us_pool, us_host = time_router(pool, 200)
     us_full, _ = time_router(0, 20)          # the "Full" pooling point of App. D.2: mean over every row
+    # the router's cost against the prompt length (Sec. 4.3 reports 0.20 ms per layer, flat from 512 to 1M
+    # tokens): one sequence of S rows, same weights; only the first and last `pool` rows are read
+    del x
+    torch.cuda.empty_cache()
+    flat = {}
+    if not args.small:
+        s_max = 1 << 20
+        xl = torch.empty(1, 1, s_max, hidden, dtype=torch.bfloat16, device=dev)
+        synth_gpu.fill_normal_bf16(xl, 4, synth.stream_id(synth.STREAM_X))
+        mode_1 = torch.zeros(1, dtype=torch.uint8, device=dev)
+        for s_len in (512, 8192, 131072, s_max):
+            cu_s = i32([0, s_len])
+            for _ in range(5):
+                F.flux_router(ctx, xl, cu_s, 1, hidden, pool, w1, None, w2, None, inner, mode_1)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(100):
+                F.flux_router(ctx, xl, cu_s, 1, hidden, pool, w1, None, w2, None, inner, mode_1)
+            e1.record()
+            torch.cuda.synchronize()
+            flat[str(s_len)] = e0.elapsed_time(e1) / 100 * 1e3
+        del xl
     router = {"us_per_layer_call": us_pool, "host_launch_us": us_host, "batch": len(lens), "pool": pool,
+              "us_per_call_vs_prompt_tokens": flat,
               "us_per_layer_call_pool_all_rows": us_full, "rows_all": T,
               "hidden": hidden, "inner": inner, "paper_ms_per_layer": 0.20}
 

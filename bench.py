@@ -38,6 +38,8 @@ def parse():
                     help="layer mask of the timed steps; all-fa / all-sa give single-kernel profiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="shrunken shapes for a quick functional check")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time one FA and one SA layer at context lengths 8K..256K (prefill and decode, batch 1)")
     return ap.parse_args()
 
 
@@ -414,6 +416,51 @@ def main():
               "us_per_layer_call_pool_all_rows": us_full, "rows_all": T,
               "hidden": hidden, "inner": inner, "paper_ms_per_layer": 0.20}
 
+    # ------------------------------------------------------------------ optional: one layer against the context length
+    sweep = None
+    if args.sweep:
+        sweep = {}
+        for s_len in (8192, 32768, 131072, 262144):
+            qs_ = torch.empty(1, s_len, HQ, D, dtype=torch.bfloat16, device=dev)
+            ks_ = torch.empty(1, s_len, HKV, D, dtype=torch.bfloat16, device=dev)
+            vs_ = torch.empty(1, s_len, HKV, D, dtype=torch.bfloat16, device=dev)
+            synth_gpu.fill_normal_bf16(qs_, 6, synth.stream_id(synth.STREAM_Q))
+            synth_gpu.fill_normal_bf16(ks_, 6, synth.stream_id(synth.STREAM_K))
+            synth_gpu.fill_normal_bf16(vs_, 6, synth.stream_id(synth.STREAM_V))
+            cache_s = F.KVCache.empty(1, HKV, s_len, D)
+            cu_s = i32([0, s_len])
+            F.flux_kv_append(ctx, cache_s, HKV, D, ks_[0], vs_[0], cu_s, s_len, s_len)
+            out_s = torch.empty(s_len, HQ, D, dtype=torch.bfloat16, device=dev)
+            outd_s = torch.empty(1, HQ, D, dtype=torch.bfloat16, device=dev)
+            row = {}
+            for name, md, reps in (("fa", 1, 3), ("sa", 0, 3)):
+                mdev = torch.full((1,), md, dtype=torch.uint8, device=dev)
+                F.flux_attn_prefill(ctx, cfg, qs_[0], cu_s, s_len, s_len, cache_s, mdev, out_s)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    F.flux_attn_prefill(ctx, cfg, qs_[0], cu_s, s_len, s_len, cache_s, mdev, out_s)
+                e1.record()
+                torch.cuda.synchronize()
+                row["prefill_%s_ms" % name] = e0.elapsed_time(e1) / reps
+                bound = s_len if md else min(s_len, NS + W)
+                for _ in range(3):
+                    F.flux_attn_decode(ctx, cfg, qs_[0, s_len - 1], bound, cache_s, mdev, outd_s)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(50):
+                    F.flux_attn_decode(ctx, cfg, qs_[0, s_len - 1], bound, cache_s, mdev, outd_s)
+                e1.record()
+                torch.cuda.synchronize()
+                row["decode_%s_us" % name] = e0.elapsed_time(e1) / 50 * 1e3
+            row["prefill_speedup_sa_over_fa"] = row["prefill_fa_ms"] / row["prefill_sa_ms"]
+            row["decode_speedup_sa_over_fa"] = row["decode_fa_us"] / row["decode_sa_us"]
+            sweep[str(s_len)] = row
+            del qs_, ks_, vs_, cache_s, out_s
+            torch.cuda.empty_cache()
+
     status = F.flux_last_device_status(ctx)
     F.flux_destroy(ctx)
 
@@ -430,7 +477,7 @@ def main():
                    "layers": L, "batch": 1, "seq_len": S, "n_q_heads": HQ, "n_kv_heads": HKV, "head_dim": D,
                    "n_sink": NS, "window": W, "sa_layers": N_SA},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
-        "prefill": prefill, "decode": decode, "router": router, "device_status": status,
+        "prefill": prefill, "decode": decode, "router": router, "context_length_sweep": sweep, "device_status": status,
     }
     print(json.dumps(line))
 

@@ -40,6 +40,10 @@ def parse():
     ap.add_argument("--small", action="store_true", help="shrunken shapes for a quick functional check")
     ap.add_argument("--sweep", action="store_true",
                     help="also time one FA and one SA layer at context lengths 8K..256K (prefill and decode, batch 1)")
+    ap.add_argument("--extra", action="store_true",
+                    help="also time the high-sparsity prefill workload (28 layers, batch 2, 65536 tokens, 28/4 heads, "
+                         "21 SA layers) and the end-to-end routed workload (32 layers, ragged batch 8K/32K/64K/128K, "
+                         "router decisions taken on the device)")
     return ap.parse_args()
 
 
@@ -461,6 +465,144 @@ def main():
             del qs_, ks_, vs_, cache_s, out_s
             torch.cuda.empty_cache()
 
+    # ------------------------------------------------------------------ optional: the two other full-size workloads
+    extra = None
+    if args.extra:
+        extra = {}
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps
+
+        # ---- high-sparsity prefill: one set of inputs serves every layer (the cost does not depend on the values)
+        L4, B4, S4, HQ4, HKV4, NS4, W4, SEED4 = 28, 2, 65536, 28, 4, 64, 2048, 3
+        mask4 = synth.random_layer_mask(SEED4, L4, 21)
+        cfg4 = F.attn_cfg(HQ4, HKV4, D, NS4, W4, 0.0, 0)
+        q4 = torch.empty(1, B4 * S4, HQ4, D, dtype=torch.bfloat16, device=dev)
+        k4 = torch.empty(1, B4 * S4, HKV4, D, dtype=torch.bfloat16, device=dev)
+        v4 = torch.empty(1, B4 * S4, HKV4, D, dtype=torch.bfloat16, device=dev)
+        synth_gpu.fill_normal_bf16(q4, SEED4, synth.stream_id(synth.STREAM_Q))
+        synth_gpu.fill_normal_bf16(k4, SEED4, synth.stream_id(synth.STREAM_K))
+        synth_gpu.fill_normal_bf16(v4, SEED4, synth.stream_id(synth.STREAM_V))
+        out4 = torch.empty(B4 * S4, HQ4, D, dtype=torch.bfloat16, device=dev)
+        caches4 = [F.KVCache.empty(B4, HKV4, S4, D) for _ in range(L4)]
+        cu4 = i32([0, S4, 2 * S4])
+        m4 = {0: torch.zeros(B4, dtype=torch.uint8, device=dev), 1: torch.ones(B4, dtype=torch.uint8, device=dev)}
+
+        def step4(mask):
+            for l in range(L4):
+                caches4[l].kv_len.zero_()
+                F.flux_kv_append(ctx, caches4[l], HKV4, D, k4[0], v4[0], cu4, B4 * S4, S4)
+                F.flux_attn_prefill(ctx, cfg4, q4[0], cu4, S4, S4, caches4[l], m4[int(mask[l])], out4)
+
+        t4_mix = timed(lambda: step4(mask4), 3)
+        t4_fa = timed(lambda: step4(np.ones(L4, dtype=np.uint8)), 2)
+        vis_sa4 = sum(min(i + 1, W4) + max(0, min(NS4, i + 1 - W4)) for i in range(S4))
+        fl_fa4 = 4.0 * D * HQ4 * B4 * pairs_fa(S4)
+        fl_sa4 = 4.0 * D * HQ4 * B4 * vis_sa4
+        n_fa4 = int(mask4.sum())
+        extra["high_sparsity_prefill"] = {
+            "workload": "%d layers, batch %d, seq_len %d, %d/%d heads, D %d, %d of %d layers SA (%d sinks + %d window), seed %d"
+                        % (L4, B4, S4, HQ4, HKV4, D, L4 - n_fa4, L4, NS4, W4, SEED4),
+            "ms_per_step_mix": t4_mix * 1e3, "ms_per_step_all_fa": t4_fa * 1e3,
+            "tokens_per_s_mix": B4 * S4 / t4_mix, "tokens_per_s_all_fa": B4 * S4 / t4_fa,
+            "all_fa_tflops": L4 * fl_fa4 / t4_fa / 1e12,
+            "speedup_mix_vs_all_fa": t4_fa / t4_mix,
+            "predicted_speedup_from_flops": L4 * fl_fa4 / (n_fa4 * fl_fa4 + (L4 - n_fa4) * fl_sa4)}
+        del q4, k4, v4, out4, caches4
+        torch.cuda.empty_cache()
+
+        # ---- end-to-end routed: per layer the router reads the query tensor and writes that layer's mode bytes
+        # on the device, append + prefill use them with no host read-back; decode reuses the cached bytes
+        L5, lens5, SEED5, n_steps5 = 32, [8192, 32768, 65536, 131072], 4, 256
+        B5, T5, smax5 = len(lens5), sum(lens5), max(lens5)
+        cap5 = smax5 + 2 * n_steps5 + 40
+        q5 = torch.empty(1, T5, HQ, D, dtype=torch.bfloat16, device=dev)
+        k5 = torch.empty(1, T5, HKV, D, dtype=torch.bfloat16, device=dev)
+        v5 = torch.empty(1, T5, HKV, D, dtype=torch.bfloat16, device=dev)
+        synth_gpu.fill_normal_bf16(q5, SEED5, synth.stream_id(synth.STREAM_Q))
+        synth_gpu.fill_normal_bf16(k5, SEED5, synth.stream_id(synth.STREAM_K))
+        synth_gpu.fill_normal_bf16(v5, SEED5, synth.stream_id(synth.STREAM_V))
+        w1_5 = torch.empty(1, L5, inner, hidden, dtype=torch.bfloat16, device=dev)
+        w2_5 = torch.empty(1, L5, 2, inner, dtype=torch.bfloat16, device=dev)
+        synth_gpu.fill_normal_bf16(w1_5, SEED5, synth.stream_id(synth.STREAM_W1), s02, 0)
+        synth_gpu.fill_normal_bf16(w2_5, SEED5, synth.stream_id(synth.STREAM_W2), s02, 0)
+        out5 = torch.empty(T5, HQ, D, dtype=torch.bfloat16, device=dev)
+        caches5 = [F.KVCache.empty(B5, HKV, cap5, D) for _ in range(L5)]
+        cu5 = i32([0] + list(np.cumsum(lens5)))
+        routed = torch.zeros(L5, B5, dtype=torch.uint8, device=dev)
+        ones5 = torch.ones(L5, B5, dtype=torch.uint8, device=dev)
+
+        def prefill5(mask_dev, route):
+            for l in range(L5):
+                if route:
+                    F.flux_router(ctx, q5, cu5, B5, hidden, pool, w1_5[0, l], None, w2_5[0, l], None, inner, mask_dev[l])
+                caches5[l].kv_len.zero_()
+                F.flux_kv_append(ctx, caches5[l], HKV, D, k5[0], v5[0], cu5, T5, smax5)
+                F.flux_attn_prefill(ctx, cfg, q5[0], cu5, smax5, smax5, caches5[l], mask_dev[l], out5)
+
+        t5_mix = timed(lambda: prefill5(routed, True), 2)
+        t5_fa = timed(lambda: prefill5(ones5, False), 1)
+        mask5 = routed.cpu().numpy()                       # read once after prefill: sizes the decode launches
+        w_fa = {n: 4.0 * D * HQ * pairs_fa(n) for n in lens5}
+        w_sa = {n: 4.0 * D * HQ * pairs_sa(n) for n in lens5}
+        work_fa = L5 * sum(w_fa.values())
+        work_mix = sum(w_fa[lens5[b]] if mask5[l, b] else w_sa[lens5[b]] for l in range(L5) for b in range(B5))
+
+        qd5 = torch.empty(1, L5, B5 * HQ, D, dtype=torch.bfloat16, device=dev)
+        kd5 = torch.empty(1, L5, B5 * HKV, D, dtype=torch.bfloat16, device=dev)
+        vd5 = torch.empty(1, L5, B5 * HKV, D, dtype=torch.bfloat16, device=dev)
+        synth_gpu.fill_normal_bf16(qd5, SEED5, synth.stream_id(synth.STREAM_QDEC))
+        synth_gpu.fill_normal_bf16(kd5, SEED5, synth.stream_id(synth.STREAM_KDEC))
+        synth_gpu.fill_normal_bf16(vd5, SEED5, synth.stream_id(synth.STREAM_VDEC))
+        outd5 = torch.empty(B5, HQ, D, dtype=torch.bfloat16, device=dev)
+        cu1_5 = i32(list(range(B5 + 1)))
+        grown = {"n": 0}
+
+        def decode5(mask_host, mask_dev):
+            grown["n"] += 1
+            for l in range(L5):
+                F.flux_kv_append(ctx, caches5[l], HKV, D, kd5[0, l], vd5[0, l], cu1_5, B5, 1)
+                # the launch is sized for the longest sequence that needs its whole cache in this layer
+                need = [lens5[b] + grown["n"] if mask_host[l, b] else min(lens5[b] + grown["n"], NS + W) for b in range(B5)]
+                F.flux_attn_decode(ctx, cfg, qd5[0, l], max(need), caches5[l], mask_dev[l], outd5)
+
+        def decode_run(mask_host, mask_dev, steps):
+            for _ in range(8):
+                decode5(mask_host, mask_dev)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                decode5(mask_host, mask_dev)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps
+
+        td5_mix = decode_run(mask5, routed, n_steps5)
+        td5_fa = decode_run(np.ones_like(mask5), ones5, n_steps5 // 4)
+        rb = 2.0 * HKV * D * 2
+        by_fa = L5 * sum(rb * n for n in lens5)
+        by_mix = sum(rb * (lens5[b] if mask5[l, b] else min(lens5[b], NS + W)) for l in range(L5) for b in range(B5))
+        extra["routed_end_to_end"] = {
+            "workload": "%d layers, ragged batch %s (%d tokens), %d/%d heads, D %d, router %d->%d->SiLU->2 with N(0, 0.02) "
+                        "weights per layer on the query tensor (pool %d + %d rows), %d sinks + %d window, seed %d, "
+                        "prefill then %d decode steps" % (L5, lens5, T5, HQ, HKV, D, hidden, inner, pool, pool, NS, W, SEED5, n_steps5),
+            "omega_msr": float((mask5 == 0).mean()),
+            "sa_layers_per_sequence": [int((mask5[:, b] == 0).sum()) for b in range(B5)],
+            "prefill_ms_routed": t5_mix * 1e3, "prefill_ms_all_fa": t5_fa * 1e3,
+            "prefill_tokens_per_s_routed": T5 / t5_mix, "prefill_tokens_per_s_all_fa": T5 / t5_fa,
+            "prefill_speedup": t5_fa / t5_mix, "prefill_predicted_speedup_from_flops": work_fa / work_mix,
+            "prefill_all_fa_tflops": work_fa / t5_fa / 1e12,
+            "decode_ms_per_step_routed": td5_mix * 1e3, "decode_ms_per_step_all_fa": td5_fa * 1e3,
+            "decode_speedup": td5_fa / td5_mix, "decode_predicted_speedup_from_bytes": by_fa / by_mix,
+            "decode_all_fa_gbs": by_fa / td5_fa / 1e9}
+        del q5, k5, v5, out5, caches5
+        torch.cuda.empty_cache()
+
     status = F.flux_last_device_status(ctx)
     F.flux_destroy(ctx)
 
@@ -477,7 +619,7 @@ def main():
                    "layers": L, "batch": 1, "seq_len": S, "n_q_heads": HQ, "n_kv_heads": HKV, "head_dim": D,
                    "n_sink": NS, "window": W, "sa_layers": N_SA},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
-        "prefill": prefill, "decode": decode, "router": router, "context_length_sweep": sweep, "device_status": status,
+        "prefill": prefill, "decode": decode, "router": router, "context_length_sweep": sweep, "extra_workloads": extra, "device_status": status,
     }
     print(json.dumps(line))
 

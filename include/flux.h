@@ -141,9 +141,13 @@ int flux_attn_prefill(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, co
  * FA streams all kv_len[b] cached rows; SA reads only rows [0, n_sink) and
  * [kv_len[b]-window, kv_len[b]) and never touches the rest (App. B.3).
  * max_kv_len: host upper bound on the number of keys any sequence of this call ATTENDS TO; the
- * largest kv_len[b] is always valid.  A caller that has read the cached mask back once and knows
- * every sequence of this layer is SA may pass min(max kv_len, n_sink + window) (both rounded up to
- * multiples of sa_block when that is set), which sizes the launch for the sparse case. */
+ * largest kv_len[b] (or the capacity) is always valid.  The split of the work over the chip is taken
+ * on the device from the lengths and mode bytes found there, so a loose bound costs only idle
+ * workgroups and a ragged batch is spread as evenly as a uniform one; the bound limits the launch
+ * and the workspace.  A caller that knows every sequence of this layer is SA may pass
+ * min(max kv_len, n_sink + window) (both rounded up to multiples of sa_block when that is set).
+ * A sequence that attends to more keys than the bound is cut at the bound (its oldest visible
+ * keys are kept) and FLUX_DEV_BAD_LENGTH is raised. */
 int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int max_kv_len,
                      const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream);
 

@@ -7,6 +7,13 @@
 // 256-thread workgroup owns one chunk and serves all query heads of the GQA group at once, so every
 // K/V row is fetched exactly once per step.
 //
+// The split is taken ON THE DEVICE from the lengths and mode bytes the call finds there: the chunk
+// size is the one that cuts the visible keys of the whole batch into about kTargetUnits workgroups,
+// and workgroup u finds its (sequence, KV head, chunk) by a prefix sum over the batch.  Every
+// workgroup with work therefore sits at the front of the grid whatever the mix of lengths and
+// modes in the batch, and a ragged batch fills the chip like a uniform one (a grid shaped by the
+// longest sequence leaves most workgroups of the short ones empty and the rest badly spread).
+//
 // Per wave, 32 keys at a time:
 //   S^T[key][q]  = K[key][:] . Q[q][:]       4 (D=128) MFMA 16x16x32 bf16 per 16 keys; the A operand
 //                                            (8 consecutive d of one key row per lane) is loaded
@@ -24,21 +31,28 @@
 
 namespace flux {
 
+// What both kernels read to agree on the split.
+struct SplitArgs {
+  const int32_t* kv_len;
+  const uint8_t* mode;
+  int batch, capacity;
+  int ring;               // != 0: the cache is a sink + ring store of a sparse layer, kv_len is logical, no mode bytes
+  int sink_lim, win_blocks, blk_shift;   // SA geometry (see sa_geom)
+  int max_keys;           // the host's bound on the keys any sequence attends to
+  int pps;                // (KV head, query block) pairs per sequence = hkv * qblocks
+};
+
 struct DecodeArgs {
   const __bf16* q;        // [B, Hq, D]
   const __bf16* k;
   const __bf16* v;
   int64_t stride_b, stride_h, stride_t;   // elements
-  const int32_t* kv_len;
-  const uint8_t* mode;
-  int capacity;
+  SplitArgs sp;
   int hq, hkv, group;     // group = hq / hkv
   int qblocks;            // ceil(group / 16)
-  int sink_lim, win_blocks, blk_shift;   // SA geometry (see sa_geom)
-  int chunk, n_chunks;
-  int ring;               // != 0: the cache is a sink + ring store of a sparse layer, kv_len is logical, no mode bytes
+  int rpu;                // partial rows per unit = min(group, 16)
   float scale_log2;       // softmax scale * log2(e)
-  float* partials;        // [B, Hq, n_chunks, D + 2]
+  float* partials;        // per pair [rpu, chunks of the pair, D + 2], pairs in unit order
   uint32_t* status;       // sticky device status word
 };
 
@@ -51,6 +65,113 @@ __device__ __forceinline__ int visible_len(int n, int md, int sink_lim, int win_
   tail_start = lo > s_end ? lo : s_end;
   sparse = (md == 0) && (tail_start > s_end);
   return sparse ? s_end + (n - tail_start) : n;
+}
+
+constexpr int kTargetShift = 10;                // about 1024 workgroups: 4 per CU, two rounds of the two that fit a CU
+constexpr int kTargetUnits = 1 << kTargetShift;
+constexpr int kMinChunk = 256;                  // 64 keys per wave: keeps the per-chunk merge a small part of the streaming
+
+// Length and mode of sequence b under the clamp: a length the host could not see (negative, or past the
+// capacity of a full cache) is cut and reported through `bad`.
+__device__ __forceinline__ void load_seq(const SplitArgs& s, int b, int& len, int& md, bool& bad) {
+  len = s.kv_len[b];
+  md = s.ring ? 0 : s.mode[b];
+  bad = len < 0 || (!s.ring && len > s.capacity);
+  len = len < 0 ? 0 : ((!s.ring && len > s.capacity) ? s.capacity : len);
+}
+
+// Visible keys of a sequence of `len` rows in mode `md`, cut at the host's bound (reported through `bad`).
+__device__ __forceinline__ int seq_visible(const SplitArgs& s, int len, int md, bool& bad, bool& sparse, int& s_end,
+                                           int& tail_start) {
+  int nv = visible_len(len, md, s.sink_lim, s.win_blocks, s.blk_shift, sparse, s_end, tail_start);
+  if (nv > s.max_keys) {
+    bad = true;
+    nv = s.max_keys;
+  }
+  return nv;
+}
+
+// The split of one call, as every wave of both kernels computes it from the lengths and mode bytes.
+struct Split {
+  int chunk;        // keys per unit: the visible keys of all pairs, counted in 128-key pieces, divided over
+                    // kTargetUnits (at least kMinChunk); the units then number at most kTargetUnits + batch * pps
+  int b;            // the sequence found (-1: the unit lies past the last one)
+  int first_unit;   // first unit of that sequence
+  int nc;           // its chunks per (KV head, query block) pair
+  int len, md;      // its clamped length and mode
+  bool any_bad;     // this lane saw a clamp trip
+};
+
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves (add within rows of 16 by
+// shifts of 1, 2, 4, 8, then carry lane 15 of each row into the next row and lane 31 into the upper half);
+// lanes without a source keep the 0 passed as the old value.  Lane 63 ends up with the total.
+__device__ __forceinline__ int wave_inclusive_sum(int x) {
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);   // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);   // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);   // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);   // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
+// unit >= 0: find the sequence whose units contain `unit`.  unit < 0: locate sequence `want_b`.
+// Lane i of the wave looks after sequences i, i + 64, ...; a batch of up to 64 takes one load per lane.
+__device__ __forceinline__ Split find_split(const SplitArgs& s, int lane, int unit, int want_b) {
+  Split r;
+  r.b = -1;
+  r.first_unit = r.nc = r.len = 0;
+  r.md = 1;
+  r.any_bad = false;
+  bool sparse;
+  int s_end, tail_start;
+  int len0 = 0, md0 = 1, nv0 = 0;                          // block 0 stays in registers for the second pass
+  int pieces = 0;
+  for (int b0 = 0; b0 < s.batch; b0 += 64) {
+    int len = 0, md = 1, nv = 0;
+    if (b0 + lane < s.batch) {
+      bool bad;
+      load_seq(s, b0 + lane, len, md, bad);
+      nv = seq_visible(s, len, md, bad, sparse, s_end, tail_start);
+      r.any_bad |= bad;
+    }
+    if (b0 == 0) {
+      len0 = len;
+      md0 = md;
+      nv0 = nv;
+    }
+    pieces += __builtin_amdgcn_readlane(wave_inclusive_sum((nv + 127) >> 7), 63);
+  }
+  const long long c128 = ((long long)pieces * s.pps + (kTargetUnits - 1)) >> kTargetShift;
+  r.chunk = c128 * 128 < kMinChunk ? kMinChunk : (int)(c128 * 128);
+
+  for (int b0 = 0, base = 0; b0 < s.batch; b0 += 64) {
+    int len = len0, md = md0, nv = nv0;
+    if (b0 > 0) {
+      len = 0, md = 1, nv = 0;
+      if (b0 + lane < s.batch) {
+        bool bad;
+        load_seq(s, b0 + lane, len, md, bad);
+        nv = seq_visible(s, len, md, bad, sparse, s_end, tail_start);
+      }
+    }
+    const int nc = (nv + r.chunk - 1) / r.chunk;
+    const int incl = wave_inclusive_sum(s.pps * nc);        // units up to and including this lane's sequence
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    const bool here = unit >= 0 ? unit < base + total : want_b < b0 + 64;
+    if (here) {                                             // wave-uniform
+      const int idx = unit >= 0 ? __builtin_popcountll(__builtin_amdgcn_ballot_w64(base + incl <= unit)) : want_b - b0;
+      const int sidx = __builtin_amdgcn_readfirstlane(idx);
+      r.b = b0 + sidx;
+      r.first_unit = base + (sidx > 0 ? __builtin_amdgcn_readlane(incl, sidx - 1) : 0);
+      r.nc = __builtin_amdgcn_readlane(nc, sidx);
+      r.len = __builtin_amdgcn_readlane(len, sidx);
+      r.md = __builtin_amdgcn_readlane(md, sidx);
+      break;
+    }
+    base += total;
+  }
+  return r;
 }
 
 template <int D, bool NT>
@@ -67,27 +188,29 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
   const int g = l >> 4, n = l & 15;
-  const int ci = blockIdx.x;
-  const int kvh = blockIdx.y / a.qblocks;
-  const int qb = blockIdx.y % a.qblocks;
-  const int b = blockIdx.z;
+  const int unit = blockIdx.x;
 
-  int len = a.kv_len[b];
-  // a length the host could not see (negative, or past the capacity of a full cache) is clamped and reported
-  if (ci == 0 && blockIdx.y == 0 && tid == 0 && (len < 0 || (!a.ring && len > a.capacity)))
-    atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
-  len = len < 0 ? 0 : ((!a.ring && len > a.capacity) ? a.capacity : len);
-  bool sparse;
+  // ---- the split: chunk size from the whole batch, then the sequence whose units contain `unit`
+  const Split sp = find_split(a.sp, l, unit, -1);
+  if (unit == 0 && w == 0 && sp.any_bad) atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
+  if (sp.b < 0) return;                                     // past the last unit: uniform for the whole workgroup
+  const int b = sp.b, chunk = sp.chunk;
+  const int local = unit - sp.first_unit;                   // < pps * nc, chunk index fastest
+  const int ci = local % sp.nc;
+  const int pair = local / sp.nc;
+  const int kvh = pair / a.qblocks;
+  const int qb = pair % a.qblocks;
+
+  bool bad_b = false, sparse;
   int s_end, tail_start;
-  const int n_vis = visible_len(len, a.ring ? 0 : a.mode[b], a.sink_lim, a.win_blocks, a.blk_shift, sparse, s_end, tail_start);
-  const int c0 = ci * a.chunk;
-  if (c0 >= n_vis) return;                                  // uniform for the whole workgroup
-  const int c1 = min(c0 + a.chunk, n_vis);
+  const int n_vis = seq_visible(a.sp, sp.len, sp.md, bad_b, sparse, s_end, tail_start);
+  const int c0 = ci * chunk;
+  const int c1 = min(c0 + chunk, n_vis);
   const int tail0 = tail_start - s_end;                     // list index p >= s_end maps to key p + tail0
   // ring store (s_end = sink_lim when sparse): that key sits in row sink_lim + (p + tail0 - sink_lim) % ring_window
   //                                                               = sink_lim + (p - sink_lim + ring0) % ring_window
-  const int ring_window = a.win_blocks << a.blk_shift;
-  const int ring0 = (a.ring && sparse) ? tail0 % ring_window : 0;
+  const int ring_window = a.sp.win_blocks << a.sp.blk_shift;
+  const int ring0 = (a.sp.ring && sparse) ? tail0 % ring_window : 0;
 
   const __bf16* kbase = a.k + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
   const __bf16* vbase = a.v + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
@@ -108,7 +231,7 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   auto key_of = [&](int p) -> int64_t {
     p = p < c1 ? p : c1 - 1;                                // keep every address inside the chunk
     if (!sparse || p < s_end) return (int64_t)p;
-    if (!a.ring) return (int64_t)p + tail0;
+    if (!a.sp.ring) return (int64_t)p + tail0;
     const int x = p - s_end + ring0;                        // < 2 * ring_window
     return (int64_t)s_end + (x >= ring_window ? x - ring_window : x);
   };
@@ -270,8 +393,9 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
         val += wgt * red[(ww * 16 + qi) * RED + e];                 // e == D+1 merges l the same way
       }
     }
-    const int head = kvh * a.group + 16 * qb + qi;
-    a.partials[(((int64_t)b * a.hq + head) * a.n_chunks + ci) * RED + e] = val;
+    // the units of one pair are consecutive: inside their block the rows run [query head][chunk], so the
+    // second kernel reads one head's chunks as one contiguous run
+    a.partials[(((int64_t)(unit - ci) * a.rpu) + (int64_t)qi * sp.nc + ci) * RED + e] = val;
   }
 }
 
@@ -279,9 +403,8 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
 // w_c = exp(m_c - max m), chunks taken in index order.
 struct CombineArgs {
   const float* partials;
-  const int32_t* kv_len;
-  const uint8_t* mode;
-  int capacity, hq, sink_lim, win_blocks, blk_shift, chunk, n_chunks, out_fp32, ring;
+  SplitArgs sp;
+  int hq, group, qblocks, rpu, out_fp32;
   float scale_log2;
   void* out;
 };
@@ -292,13 +415,13 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
   __shared__ float wgt[D];
   __shared__ float red[4];
   const int d = threadIdx.x, head = blockIdx.x, b = blockIdx.y;
-  int len = a.kv_len[b];
-  len = len < 0 ? 0 : ((!a.ring && len > a.capacity) ? a.capacity : len);
-  bool sparse;
-  int s_end, tail_start;
-  const int n_vis = visible_len(len, a.ring ? 0 : a.mode[b], a.sink_lim, a.win_blocks, a.blk_shift, sparse, s_end, tail_start);
-  const int nc = min((n_vis + a.chunk - 1) / a.chunk, a.n_chunks);   // chunks the launch covered
-  const float* base = a.partials + ((int64_t)b * a.hq + head) * a.n_chunks * RED;
+  const int lane = d & 63;
+  // ---- the same split the first kernel took
+  const Split sp = find_split(a.sp, lane, -1, b);
+  const int nc = sp.nc, first_unit = sp.first_unit;
+  const int hh = head % a.group;
+  const int64_t unit0 = first_unit + (int64_t)((head / a.group) * a.qblocks + hh / 16) * nc;
+  const float* base = a.partials + (unit0 * a.rpu + (int64_t)(hh % 16) * nc) * RED;
   // ---- maximum over the chunks (threads take chunks round-robin, then a block reduction)
   float m = -INFINITY;
   for (int c = d; c < nc; c += D) m = fmaxf(m, base[c * RED + D]);
@@ -336,21 +459,21 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
 }
 
 DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len) {
-  // Aim for about 1024 workgroups (4 per CU, two rounds of the two that fit a CU) with chunks of at
-  // least 256 keys (64 per wave), so that the per-chunk merge stays a small fraction of the streaming.
-  const long long pairs = (long long)batch * cfg.n_kv_heads * ((cfg.n_q_heads / cfg.n_kv_heads + 15) / 16);
-  long long total = pairs * (long long)(max_kv_len > 0 ? max_kv_len : 1);
-  long long chunk = (total + 1023) / 1024;
-  chunk = ((chunk + 127) / 128) * 128;
-  if (chunk < 256) chunk = 256;
+  // Upper bound on the units the device-side split can produce: kTargetUnits + one per pair from the chunk
+  // size it picks, and no more than the pairs times the chunks of the longest list at the smallest chunk.
   DecodePlan p;
-  p.chunk = (int)chunk;
-  p.n_chunks = (int)(((long long)(max_kv_len > 0 ? max_kv_len : 1) + chunk - 1) / chunk);
+  const int group = cfg.n_q_heads / cfg.n_kv_heads;
+  p.pps = cfg.n_kv_heads * ((group + 15) / 16);
+  p.rpu = group < 16 ? group : 16;
+  const long long pairs = (long long)batch * p.pps;
+  const long long by_len = pairs * (((long long)(max_kv_len > 0 ? max_kv_len : 1) + kMinChunk - 1) / kMinChunk);
+  const long long by_target = kTargetUnits + pairs;
+  p.units = (int)(by_len < by_target ? by_len : by_target);
   return p;
 }
 
-size_t decode_partials_bytes(const flux_attn_cfg& cfg, int batch, const DecodePlan& p) {
-  return (size_t)batch * cfg.n_q_heads * p.n_chunks * (cfg.head_dim + 2) * sizeof(float);
+size_t decode_partials_bytes(const flux_attn_cfg& cfg, const DecodePlan& p) {
+  return (size_t)p.units * p.rpu * (cfg.head_dim + 2) * sizeof(float);
 }
 
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
@@ -364,24 +487,26 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   a.stride_b = cache.stride_b;
   a.stride_h = cache.stride_h;
   a.stride_t = cache.stride_t;
-  a.kv_len = cache.kv_len;
-  a.mode = mode;
-  a.capacity = cache.capacity;
+  const SaGeom geom = sa_geom(cfg);
+  a.sp.kv_len = cache.kv_len;
+  a.sp.mode = mode;
+  a.sp.batch = cache.batch;
+  a.sp.capacity = cache.capacity;
+  a.sp.ring = ring;
+  a.sp.sink_lim = geom.sink_lim;
+  a.sp.win_blocks = geom.win_blocks;
+  a.sp.blk_shift = geom.shift;
+  a.sp.max_keys = max_kv_len;
+  a.sp.pps = plan.pps;
   a.hq = cfg.n_q_heads;
   a.hkv = cfg.n_kv_heads;
   a.group = cfg.n_q_heads / cfg.n_kv_heads;
   a.qblocks = (a.group + 15) / 16;
-  const SaGeom geom = sa_geom(cfg);
-  a.sink_lim = geom.sink_lim;
-  a.win_blocks = geom.win_blocks;
-  a.blk_shift = geom.shift;
-  a.chunk = plan.chunk;
-  a.n_chunks = plan.n_chunks;
-  a.ring = ring;
+  a.rpu = plan.rpu;
   a.scale_log2 = scale * kLog2e;
   a.partials = c.partials;
   a.status = c.status;
-  const dim3 grid(plan.n_chunks, cfg.n_kv_heads * a.qblocks, cache.batch);
+  const dim3 grid(plan.units);
   // K and V bytes one call may read, against the 256 MB last-level cache
   const bool nt = 4.0 * cache.batch * cfg.n_kv_heads * cfg.head_dim * (double)max_kv_len > 256.0 * 1024 * 1024;
   if (cfg.head_dim == 128) {
@@ -396,17 +521,12 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
 
   CombineArgs ca;
   ca.partials = c.partials;
-  ca.kv_len = cache.kv_len;
-  ca.mode = mode;
-  ca.capacity = cache.capacity;
+  ca.sp = a.sp;
   ca.hq = cfg.n_q_heads;
-  ca.sink_lim = geom.sink_lim;
-  ca.win_blocks = geom.win_blocks;
-  ca.blk_shift = geom.shift;
-  ca.chunk = plan.chunk;
-  ca.n_chunks = plan.n_chunks;
+  ca.group = a.group;
+  ca.qblocks = a.qblocks;
+  ca.rpu = plan.rpu;
   ca.out_fp32 = cfg.out_dtype;
-  ca.ring = ring;
   ca.scale_log2 = a.scale_log2;
   ca.out = out;
   const dim3 cgrid(cfg.n_q_heads, cache.batch);

@@ -67,7 +67,7 @@ const char* flux_strerror(int code) {
 size_t flux_workspace_needed(const flux_attn_cfg* cfg, int batch, int max_kv_len) {
   if (check_cfg(cfg) != FLUX_OK || batch <= 0 || max_kv_len < 0) return 0;
   const DecodePlan p = plan_decode(*cfg, batch, max_kv_len);
-  return kHeaderBytes + kSmallBytes + decode_partials_bytes(*cfg, batch, p);
+  return kHeaderBytes + kSmallBytes + decode_partials_bytes(*cfg, p);
 }
 
 int flux_create(flux_ctx** out, int device, size_t workspace_bytes) {
@@ -192,7 +192,7 @@ int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int
   if (max_kv_len > cache->capacity) return FLUX_ECAPACITY;
   if (!aligned16(q) || !aligned16(out)) return FLUX_EINVAL;
   const DecodePlan p = plan_decode(*cfg, cache->batch, max_kv_len);
-  if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, cache->batch, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
+  if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
   const hipError_t e = launch_decode(ctx->c, *cfg, q, max_kv_len, *cache, mode, 0, out, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
@@ -247,7 +247,7 @@ int flux_attn_decode_ring(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q
   if (!aligned16(q) || !aligned16(out)) return FLUX_EINVAL;
   const int n_keys = (int)ring_rows;                         // the most any sequence attends to
   const DecodePlan p = plan_decode(*cfg, ring->batch, n_keys);
-  if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, ring->batch, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
+  if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
   const hipError_t e = launch_decode(ctx->c, *cfg, q, n_keys, *ring, nullptr, 1, out, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);

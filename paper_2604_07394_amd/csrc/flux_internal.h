@@ -66,11 +66,12 @@ hipError_t launch_kv_compact_ring(const flux_kv_cache& src, const flux_kv_cache&
                                   int window, hipStream_t s);
 
 struct DecodePlan {
-  int chunk;        // keys per workgroup
-  int n_chunks;     // grid.x
+  int units;        // workgroups launched: an upper bound on the units of the split the device takes
+  int pps;          // (KV head, query block) pairs per sequence
+  int rpu;          // partial rows each unit writes
 };
 DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len);
-size_t decode_partials_bytes(const flux_attn_cfg& cfg, int batch, const DecodePlan& p);
+size_t decode_partials_bytes(const flux_attn_cfg& cfg, const DecodePlan& p);
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
                          const flux_kv_cache& cache, const uint8_t* mode, int ring, void* out, hipStream_t s);
 

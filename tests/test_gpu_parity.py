@@ -105,7 +105,8 @@ class Layer:
         torch.cuda.synchronize()
         qf = O.bf16_to_f64(qb)
         ref = np.stack([O.attention(qf[b][None], self.ocache.k[b], self.ocache.v[b], int(modes[b]), self.n_sink,
-                                    self.window, block=self.block)[0] for b in range(self.B)])
+                                    self.window, block=self.block)[0] if self.lens[b] else np.zeros((self.hq, self.d))
+                        for b in range(self.B)])
         return out.cpu().numpy(), ref
 
 
@@ -263,6 +264,44 @@ def test_decode_ragged_multi_chunk(F, ctx, d, hq, hkv):
         got, ref = lay.decode(qb.reshape(4, hq, d), modes)
         for b in range(4):
             H.assert_close(got[b], ref[b], f"decode step {step} seq {b} (len {lay.lens[b]})")
+
+
+def test_decode_wide_ragged_batch_more_sequences_than_lanes(F, ctx):
+    """70 sequences (the device-side split walks the batch 64 at a time) with lengths from 0 to a few
+    thousand and alternating modes: every sequence is found by the prefix sum and merged with its own chunks."""
+    B, hq, hkv, d = 70, 4, 1, 128
+    rng = np.random.default_rng(5)
+    lens = [int(x) for x in rng.integers(0, 2600, size=B)]
+    lens[3], lens[64], lens[69] = 0, 2599, 1
+    modes = [FA if (b * 7) % 3 else SA for b in range(B)]
+    lay = Layer(F, ctx, 35, B, hq, hkv, d, 2700, 16, 200)
+    _, kb, vb = lay.new_tokens(lens)
+    lay.append(kb, vb, lens)
+    qb = lay._draw(synth.STREAM_Q, B, hq, None)
+    got, ref = lay.decode(qb.reshape(B, hq, d), modes, max_kv_len=2700)
+    for b in range(B):
+        if lens[b]:
+            H.assert_close(got[b], ref[b], f"wide batch seq {b} (len {lens[b]}, mode {modes[b]})")
+        else:
+            assert not got[b].any()
+    assert F.flux_last_device_status(ctx) == 0
+
+
+def test_decode_long_ragged_batch_chunk_above_minimum(F, ctx):
+    """Enough visible keys in the batch that the device picks a chunk above its minimum, with one long,
+    one medium and one short sequence sharing the call."""
+    lens = [100000, 40000, 5000]
+    modes = [FA, FA, SA]
+    lay = Layer(F, ctx, 36, 3, 8, 2, 128, 100010, 64, 1000)
+    _, kb, vb = lay.new_tokens(lens)
+    lay.append(kb, vb, lens)
+    qb, kb, vb = lay.new_tokens([1, 1, 1])
+    lay.append(kb, vb, [1, 1, 1])
+    got, ref = lay.decode(qb.reshape(3, 8, 128), modes)
+    for b in range(3):
+        H.assert_close(got[b], ref[b], f"long ragged seq {b}")
+    again, _ = lay.decode(qb.reshape(3, 8, 128), modes, max_kv_len=100010)     # a looser host bound changes nothing
+    assert np.array_equal(got, again)
 
 
 def test_decode_equals_last_prefill_row_on_gpu(F, ctx):
@@ -472,6 +511,13 @@ def test_inconsistent_lengths_are_clamped_and_flagged(F, ctx):
     assert np.array_equal(out.cpu().numpy(), good)                    # clamped to the capacity
     assert F.flux_last_device_status(ctx) & F.FLUX_DEV_BAD_LENGTH
     assert F.flux_last_device_status(ctx) == 0                        # reading clears it
+    # a host bound below what a sequence attends to: the visible list is cut at the bound and the cut reported
+    lay.cache.kv_len.fill_(256)
+    F.flux_attn_decode(ctx, lay.cfg, H.bits_to_torch(q1), 100, lay.cache, u8([FA]), out)
+    torch.cuda.synchronize()
+    cut = O.attention(O.bf16_to_f64(q1), lay.ocache.k[0][:100], lay.ocache.v[0][:100], FA, 8, 64)[0]
+    H.assert_close(out[0].cpu().numpy(), cut, "decode cut at the host bound")
+    assert F.flux_last_device_status(ctx) & F.FLUX_DEV_BAD_LENGTH
     lay.cache.kv_len.fill_(50)                                        # fewer cached positions than queries
     outp = torch.full((100, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
     F.flux_attn_prefill(ctx, lay.cfg, H.bits_to_torch(qb[:100]), cu([100]), 100, 256, lay.cache, u8([SA]), outp)

@@ -69,6 +69,7 @@ __device__ __forceinline__ int visible_len(int n, int md, int sink_lim, int win_
 
 constexpr int kTargetShift = 10;                // about 1024 workgroups: 4 per CU, two rounds of the two that fit a CU
 constexpr int kTargetUnits = 1 << kTargetShift;
+constexpr int kResidentUnits = 512;             // workgroups the chip holds at once (two per CU at this register count)
 constexpr int kMinChunk = 256;                  // 64 keys per wave: keeps the per-chunk merge a small part of the streaming
 
 // Length and mode of sequence b under the clamp: a length the host could not see (negative, or past the
@@ -144,6 +145,17 @@ __device__ __forceinline__ Split find_split(const SplitArgs& s, int lane, int un
   }
   const long long c128 = ((long long)pieces * s.pps + (kTargetUnits - 1)) >> kTargetShift;
   r.chunk = c128 * 128 < kMinChunk ? kMinChunk : (int)(c128 * 128);
+  // If a chunk of about twice that size cuts the batch into one nearly full round of the workgroups the chip
+  // holds at once, take it: a single round of equal workgroups pays the start and the merge of a workgroup
+  // once instead of twice (3 us of a 30 us call).  Uniform batches do; a ragged one usually spills a few
+  // units into a second round, which would double the time, and a short list (a sparse layer) leaves much
+  // of the round empty: both keep the smaller chunk.
+  if (s.batch <= 64) {
+    const long long o128 = ((long long)pieces * s.pps + (kResidentUnits - 1)) / kResidentUnits;
+    const int big = o128 * 128 < kMinChunk ? kMinChunk : (int)(o128 * 128);
+    const int units = __builtin_amdgcn_readlane(wave_inclusive_sum(s.pps * ((nv0 + big - 1) / big)), 63);
+    if (units <= kResidentUnits && units > kResidentUnits - kResidentUnits / 10) r.chunk = big;
+  }
 
   for (int b0 = 0, base = 0; b0 < s.batch; b0 += 64) {
     int len = len0, md = md0, nv = nv0;

@@ -247,6 +247,39 @@ def test_prefill_is_deterministic(F, ctx):
     assert np.array_equal(a, b)
 
 
+def _scaled_bits(bits, factor):
+    """bf16 bit patterns times a per-row factor, rounded to bf16 again (input preparation only)."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).float()
+    t = (t * torch.from_numpy(np.asarray(factor, dtype=np.float32)).reshape(-1, 1, 1)).to(torch.bfloat16)
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("shape", ["rising", "falling", "spikes"])
+def test_prefill_and_decode_softmax_range(F, ctx, shape):
+    """Scores that move by hundreds of powers of two along the keys: key norms that rise or fall 40-fold over
+    the prompt, and isolated keys 60 times larger than their neighbours.  The running reference of the online
+    softmax has to follow (rescale) without overflow, and rows whose early keys end up negligible must not
+    lose the late ones."""
+    S, hq, hkv, d = 1100, 4, 1, 128
+    lay = Layer(F, ctx, 71, 1, hq, hkv, d, S + 8, 16, 300)
+    qb, kb, vb = lay.new_tokens([S])
+    j = np.arange(S, dtype=np.float64)
+    if shape == "rising":
+        f = 0.25 + 10.0 * j / S
+    elif shape == "falling":
+        f = 10.0 - 9.75 * j / S
+    else:
+        f = np.where((j % 97) == 41, 15.0, 0.25)
+    kb = _scaled_bits(kb, f)
+    qb = _scaled_bits(qb, np.full(S, 2.0))
+    lay.append(kb, vb, [S])
+    for mode in (FA, SA):
+        got, ref = lay.prefill(qb, [S], [mode])
+        H.assert_close(got, ref, f"{shape} keys, mode {mode}")
+    dec, dref = lay.decode(qb[S - 1][None], [FA])
+    H.assert_close(dec, dref, f"{shape} keys, decode")
+
+
 # ----------------------------------------------------------------------------- decode
 
 @pytest.mark.parametrize("d,hq,hkv", [(128, 8, 2), (128, 7, 1), (64, 8, 2), (128, 40, 2)])

@@ -36,7 +36,7 @@ struct PrefillArgs {
 };
 
 constexpr int BM = 128;   // query rows per workgroup
-constexpr float kRescaleThreshold = 8.0f;   // log2 units: rescale O only when the row max grew by > 2^8
+constexpr float kWeightGuard = 1073741824.0f;   // 2^30: a block whose weights sum past this moves the softmax reference
 
 // One wave-wide direct global -> LDS transfer: every lane fetches its own 16 bytes, the 64 pieces land
 // at lds_base + 16 * lane.  Issued as inline assembly so that the compiler does not serialise later LDS
@@ -215,7 +215,8 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   for (int db = 0; db < DB; ++db)
     v_rd[db] = KTILE + (4 * g + (s16 >> 2)) * ROWB + ((db ^ v_xr) * 64) + (2 * beta + ((s16 & 3) >> 1)) * 16 + (s16 & 1) * 8;
 
-  float m_ref = -INFINITY, l_run = 0.f;                      // m_ref: the maximum the exponents refer to
+  float m_ref = -INFINITY, l_run = 0.f;                      // m_ref: the score the exponents refer to
+  bool all_ref = false;                                      // wave-uniform: every row of the wave has a reference
   f32x16 o[DB];
 #pragma unroll
   for (int i = 0; i < DB; ++i)
@@ -265,42 +266,57 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
           s[kb][r] = vis ? s[kb][r] : -INFINITY;
         }
     }
-    // ---- online softmax for this lane's query column, with lazy rescaling: the accumulators keep
-    // referring to m_ref until the running maximum has grown by more than 2^kRescaleThreshold
-    float mloc = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-      for (int r = (kb == 0 ? 1 : 0); r < 16; ++r) mloc = fmaxf(mloc, s[kb][r]);
-    mloc = max_across_halves(mloc);
-    const float m_new = fmaxf(m_ref, mloc);
-    const bool grow = (m_new - m_ref) * a.scale_log2 > kRescaleThreshold;   // false while both are -inf
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-      const float alpha = fast_exp2((m_ref - m_new) * a.scale_log2);        // 0 on the first block
-      const float al = m_new == -INFINITY ? 1.f : alpha;
-      l_run *= al;
-#pragma unroll
-      for (int db = 0; db < DB; ++db) o[db] *= al;
-      m_ref = m_new;
-    }
-    const float mneg = m_ref == -INFINITY ? 0.f : -m_ref * a.scale_log2;    // a row that has seen no key yet
+    // ---- online softmax for this lane's query column.  The weights are taken against the reference m_ref
+    // the accumulators already refer to, WITHOUT looking for the block's maximum first: any reference gives
+    // the same quotient, and fp32 / bf16 keep their relative precision over the whole exponent range.  Only
+    // when a row has no reference yet, or some weight of the block left the guarded range (or overflowed),
+    // does the wave take the block's maximum, move the reference there (rescaling l and O) and redo the
+    // weights.  In the steady state the maximum, its cross-lane step and the rescale test are not executed.
     bf16x8 pf[NKB][2];
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    float l_blk;
+    auto weights = [&](float mneg) {
+      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+      l_blk = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
+      for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        uint32_t pk[4];
+        for (int c = 0; c < 2; ++c) {
+          uint32_t pk[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const float p0 = fast_exp2(__builtin_fmaf(s[kb][8 * c + 2 * t], a.scale_log2, mneg));
-          const float p1 = fast_exp2(__builtin_fmaf(s[kb][8 * c + 2 * t + 1], a.scale_log2, mneg));
-          pk[t] = pack_bf16(p0, p1);
-          // the denominator sums the same rounded weights the numerator uses
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[t]), ones, l_run, false);
+          for (int t = 0; t < 4; ++t) {
+            const float p0 = fast_exp2(__builtin_fmaf(s[kb][8 * c + 2 * t], a.scale_log2, mneg));
+            const float p1 = fast_exp2(__builtin_fmaf(s[kb][8 * c + 2 * t + 1], a.scale_log2, mneg));
+            pk[t] = pack_bf16(p0, p1);
+            // the denominator sums the same rounded weights the numerator uses
+            l_blk = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[t]), ones, l_blk, false);
+          }
+          pf[kb][c] = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
         }
-        pf[kb][c] = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
+    };
+    bool redo = !all_ref;                                                      // some row has no reference yet
+    if (!redo) {
+      weights(-m_ref * a.scale_log2);
+      redo = __builtin_amdgcn_ballot_w64(!(l_blk < kWeightGuard)) != 0;        // also true for +inf
+    }
+    if (redo) {
+      float mloc = s[0][0];
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+        for (int r = (kb == 0 ? 1 : 0); r < 16; ++r) mloc = fmaxf(mloc, s[kb][r]);
+      mloc = max_across_halves(mloc);
+      const float m_new = fmaxf(m_ref, mloc);
+      if (m_new > m_ref) {                                                     // false while both are -inf
+        const float al = fast_exp2((m_ref - m_new) * a.scale_log2);            // 0 for a row's first reference
+        l_run *= al;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[db] *= al;
+        m_ref = m_new;
       }
+      weights(m_ref == -INFINITY ? 0.f : -m_ref * a.scale_log2);               // a row that has seen no key yet
+      all_ref = __builtin_amdgcn_ballot_w64(m_ref == -INFINITY) == 0;
+    }
+    l_run += l_blk;
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb)

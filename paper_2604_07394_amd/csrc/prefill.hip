@@ -1,16 +1,22 @@
 // flux_attn_prefill: tiled causal GQA attention on bf16 MFMA, Full (Eq. 1) or Sparse (Eq. 2 with the
 // sink + window subset of Sec. 4.1 / App. C.3), chosen per sequence by the cached mode byte.
 //
-// Shape of the computation (one workgroup = 128 query rows of one head, 4 waves x 32 rows):
+// Shape of the computation (one workgroup = 128 query rows of one head, 4 waves x 32 rows = 2 column blocks
+// of 16 queries):
 //   for each VISITED 64-key block (FA: all blocks up to the diagonal; SA: the sink blocks and the
 //   blocks that intersect the tile's window, nothing else: hidden blocks are skipped, not masked)
-//     S^T[key][q]  = K[key][:] . Q[q][:]     MFMA 32x32x16 bf16, A = K rows from LDS, B = Q in registers
-//     online softmax along keys.  S is kept TRANSPOSED so that one lane owns one query column:
-//     the running max / sum are per-lane scalars, 16 of the 32 keys of a block sit in the lane's own
-//     accumulator registers, and the only cross-lane step is one half-wave swap.
-//     O^T[d][q]   += V^T[d][key] . P^T[key][q]   the accumulator layout of S^T is already the B-operand
-//     layout of this product, so P never moves between lanes; V^T comes from row-major LDS through
-//     the transposing LDS read.
+//     S^T[key][q]  = K[key][:] . Q[q][:]     MFMA 16x16x32 bf16, A = K rows from LDS, B = Q in registers
+//     online softmax along keys.  S is kept TRANSPOSED: a query column belongs to the 4 lanes
+//     (n, g = 0..3), each holding 4 of a 16-key block's scores in its accumulator registers, so the
+//     running reference is a per-lane scalar and the row sum a per-lane partial that is only combined
+//     across the 4 lanes at the end.
+//     O^T[d][q]   += V^T[d][key] . P^T[key][q]   the accumulator layout of two 16-key blocks of S^T is the
+//     B-operand layout of this product for 32 keys (keys taken in the order 4g..4g+3, 16+4g..16+4g+3), so
+//     P never moves between lanes; V^T comes from row-major LDS through the transposing LDS read, its
+//     keys in the same order.
+// The 16x16x32 form is used because it is the one this chip sustains: a loop of nothing but MFMAs on
+// random bf16 data reaches 2030-2280 TFLOP/s with it and 1170-1450 with 32x32x16, whatever the number of
+// independent accumulators.
 // Only blocks that straddle the causal diagonal or a window / sink edge evaluate the element mask.
 #include "flux_internal.h"
 
@@ -49,12 +55,19 @@ __device__ __forceinline__ void dma16(const char* base /*uniform*/, int lane_off
 template <int D, int NKB>                 // NKB: 32-key blocks per iteration (BN = 32 * NKB keys)
 __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillArgs a) {
   constexpr int BN = 32 * NKB;
-  constexpr int KC = D / 16;              // MFMA k-steps over the head dimension (QK^T)
-  constexpr int DB = D / 32;              // 32-wide output blocks over the head dimension (PV)
+  constexpr int KC = D / 32;              // MFMA k-steps over the head dimension (QK^T)
+  constexpr int DB = D / 16;              // 16-wide output blocks over the head dimension (PV)
+  constexpr int KB = BN / 16;             // 16-key blocks of S^T per iteration
+  constexpr int KS = BN / 32;             // 32-key steps of the PV product per iteration
   constexpr int CPR = D / 8;              // 16-byte chunks per row
   constexpr int ROWB = D * 2;             // bytes per K/V row
-  constexpr int KPITCH = ROWB + 16;       // K tile: rows padded by one chunk (conflict-free 16-byte reads)
-  constexpr int NKI = (BN * (CPR + 1) + 63) / 64;   // wave-wide 1 KB transfers per K tile (padding chunks included)
+  // K tile: rows padded by two chunks.  A wave-wide 16-byte LDS read is served in four passes of 16 lanes, and
+  // within lanes 0..31 the passes are {0-3, 12-15, 20-27} and {4-11, 16-19, 28-31} (measured with the bank
+  // conflict counter); with lane (n, g) at row n, chunk g, a pitch of 8 banks mod 64 keeps every pass on 64
+  // distinct banks, a pitch of 4 banks (one padding chunk) does not
+  constexpr int KPAD = 2;
+  constexpr int KPITCH = ROWB + 16 * KPAD;
+  constexpr int NKI = (BN * (CPR + KPAD) + 63) / 64;   // wave-wide 1 KB transfers per K tile (padding chunks included)
   constexpr int NVI = BN * CPR / 64;         // wave-wide 1 KB transfers per V tile
   constexpr int KTILE = NKI * 1024;       // bytes (whole transfers; the tail of the last one is unused)
   constexpr int VTILE = BN * ROWB;        // V tile: unpadded rows, chunk index XOR-swizzled by the row
@@ -69,7 +82,7 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l = tid & 63;
-  const int g = l >> 5, n = l & 31;
+  const int g = l >> 4, n = l & 15;
   // ---- which (sequence, head, query tile) this workgroup owns.  Workgroups go to the 8 XCDs round-robin
   // by linear id, and each XCD has its own L2.  All query heads and query tiles that read one
   // (sequence, KV head) pair are therefore given ids of one residue mod 8, heaviest tiles first and the
@@ -126,19 +139,26 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   const int i_w_min = pos0 + r_w0;
   const int i_w_max = pos0 + min(r_w0 + 31, n_q - 1);       // < i_w_min if the wave has no valid row
   const bool wave_active = r_w0 < n_q;
-  const int r_mine = min(r_w0 + n, n_q - 1);                 // clamped row of this lane's query
-  const int i_mine = pos0 + r_w0 + n;                        // its position (unclamped)
-  // first key of the SA window of this lane's row, of the wave's first row and of its last row
-  const int w_lo_mine = window_start(i_mine, a.blk_shift, a.win_blocks);
+  // this lane's two query rows (column n of column block qb): clamped row, unclamped position, and the
+  // first key of the row's SA window
+  int r_mine[2], i_mine[2], w_lo_mine[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    r_mine[qb] = min(r_w0 + 16 * qb + n, n_q - 1);
+    i_mine[qb] = pos0 + r_w0 + 16 * qb + n;
+    w_lo_mine[qb] = window_start(i_mine[qb], a.blk_shift, a.win_blocks);
+  }
+  // first key of the SA window of the wave's first row and of its last row
   const int w_lo_first = window_start(i_w_min, a.blk_shift, a.win_blocks);
   const int w_lo_last = window_start(max(i_w_max, i_w_min), a.blk_shift, a.win_blocks);
 
-  // ---- Q operand: lane (n, g) holds d = 16*kc + 8*g .. +7 of its query row
-  bf16x8 qf[KC];
-  {
-    const __bf16* qrow = a.q + ((int64_t)(q_begin + r_mine) * a.hq + h) * D;
+  // ---- Q operand: lane (n, g) holds d = 32*kc + 8*g .. +7 of its two query rows
+  bf16x8 qf[2][KC];
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(qrow + 16 * kc + 8 * g);
+  for (int qb = 0; qb < 2; ++qb) {
+    const __bf16* qrow = a.q + ((int64_t)(q_begin + r_mine[qb]) * a.hq + h) * D;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) qf[qb][kc] = *(const bf16x8*)(qrow + 32 * kc + 8 * g);
   }
 
   // ---- visited key blocks: [0, n_a) and [win0, win0 + n_b)
@@ -163,15 +183,18 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   // ---- direct global -> LDS transfers.  One transfer moves 64 x 16 bytes to 1 KB of consecutive LDS;
   // which (row, chunk) a lane fetches decides where that chunk lands.  Per lane, the row and chunk of
   // each of this wave's transfers are fixed for the whole kernel.
-  // K: LDS slot p = 64*I + l of transfer I holds (row p/(CPR+1), chunk p%(CPR+1)); the padding slot of a
-  // row re-fetches its last chunk.  V: transfer I covers rows I*RPI .. +RPI-1; lane l sits at
+  // K: LDS slot p = 64*I + l of transfer I holds (row p/(CPR+KPAD), chunk p%(CPR+KPAD)); the padding slots of a
+  // row re-fetch its last chunk.  V: transfer I covers rows I*RPI .. +RPI-1; lane l sits at
   // (row l/CPR, physical chunk l%CPR) and fetches the logical chunk that the swizzle maps there.
   auto k_slot = [&](int t, int rmax) {
     const int p = 64 * (w + 4 * t) + l;
-    return min(min(p / (CPR + 1), BN - 1), rmax) * pitch_g + min(p % (CPR + 1), CPR - 1) * 16;
+    return min(min(p / (CPR + KPAD), BN - 1), rmax) * pitch_g + min(p % (CPR + KPAD), CPR - 1) * 16;
   };
   const int v_lrow = l / CPR;
-  const int v_swz = D == 128 ? ((v_lrow & 3) << 2) : (((v_lrow >> 1) & 1) << 2);
+  // the 32-byte units of a V row are XOR-swizzled by the row (D = 128: row & 7; D = 64, two rows per 64
+  // banks: (row >> 1) & 3), which makes the transposing reads below conflict-free; the row of transfer
+  // w + 4t, lane l is (w + 4t) * RPI + l / CPR, so the swizzle is a per-lane constant
+  const int v_swz = D == 128 ? ((4 * (w & 1) + v_lrow) << 1) : (((v_lrow >> 1) & 3) << 1);
   const int v_chunk = (l % CPR) ^ v_swz;
   auto v_slot = [&](int t, int rmax) { return min((w + 4 * t) * RPI + v_lrow, rmax) * pitch_g + v_chunk * 16; };
   int k_off[KPW], v_off[VPW];                                // byte offsets inside a tile that is fully cached
@@ -207,21 +230,23 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
   };
 
   // ---- per-lane LDS read offsets (bytes, relative to the stage)
-  const int k_rd = n * KPITCH + g * 16;                       // K fragment: row 32*kb + n, chunk 2*kc + g
-  const int s16 = l & 15, beta = (l >> 4) & 1;
-  const int v_xr = D == 128 ? (s16 >> 2) : ((s16 >> 3) & 1);
-  int v_rd[DB];                                              // V^T fragment for output block db
+  const int k_rd = n * KPITCH + g * 16;                       // K fragment: row 16*kb + n, d = 32*kc + 8*g ..
+  // V^T fragment for output block db: the transposing read of lane (n, g) addresses row 4*g + n/4, columns
+  // 16*db + 4*(n%4) .. +3, and returns V^T[16*db + n][keys 4g .. 4g+3] of the 16-row group
+  const int v_row = 4 * g + (n >> 2);
+  const int v_xr = D == 128 ? (v_row & 7) : ((v_row >> 1) & 3);
+  int v_rd[DB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-    v_rd[db] = KTILE + (4 * g + (s16 >> 2)) * ROWB + ((db ^ v_xr) * 64) + (2 * beta + ((s16 & 3) >> 1)) * 16 + (s16 & 1) * 8;
+  for (int db = 0; db < DB; ++db) v_rd[db] = KTILE + v_row * ROWB + ((db ^ v_xr) * 32) + (n & 3) * 8;
 
-  float m_ref = -INFINITY, l_run = 0.f;                      // m_ref: the score the exponents refer to
+  float m_ref[2] = {-INFINITY, -INFINITY};                   // the score the exponents of a row refer to
+  float l_run[2] = {0.f, 0.f};                               // this lane's part of the row sums
   bool all_ref = false;                                      // wave-uniform: every row of the wave has a reference
-  f32x16 o[DB];
+  f32x4 o[DB][2];
 #pragma unroll
   for (int i = 0; i < DB; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+    for (int qb = 0; qb < 2; ++qb) o[i][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   if (n_iter > 0) issue_tile(0, 0);
   for (int it = 0; it < n_iter; ++it) {
@@ -244,113 +269,153 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillA
     if (skip) continue;
 
     FLUX_LDS char* st = (FLUX_LDS char*)smem + stage * STAGE;
-    // ---- S^T = K Q^T
-    f32x16 s[NKB];
+    // Order of the block, written out so that every LDS read is issued well before its use (the fences keep
+    // the compiler from sinking the reads back to their uses):
+    //   K fragments of both halves | S^T half 0 | V fragments of half 0 | S^T half 1 | weights |
+    //   V fragments of half 1 | O^T += half 0 | O^T += half 1
+    f32x4 s[KB][2];              // s[kb][qb][i]: key j0 + 16*kb + 4*g + i against query row (qb, n)
+    bf16x8 pf[2][KS];            // pf[qb][ks]: weights of keys 32*ks + {4g..4g+3, 16+4g..16+4g+3}, as a B operand
+    bf16x8 kf[KB][KC];
+    bf16x8 vf[KS][DB];
+    auto load_k = [&](int ks) {
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb) {
+      for (int kb = 2 * ks; kb < 2 * ks + 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-      bf16x8 kf[KC];
+        for (int kc = 0; kc < KC; ++kc) kf[kb][kc] = *(FLUX_LDS bf16x8*)(st + k_rd + 16 * kb * KPITCH + 64 * kc);
+    };
+    auto load_v = [&](int ks) {
 #pragma unroll
-      for (int kc = 0; kc < KC; ++kc) kf[kc] = *(FLUX_LDS bf16x8*)(st + k_rd + 32 * kb * KPITCH + 32 * kc);
+      for (int db = 0; db < DB; ++db) {
+        FLUX_LDS char* vp = st + v_rd[db] + 32 * ks * ROWB;
+        const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)vp);
+        const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)(vp + 16 * ROWB));
+        vf[ks][db] = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    };
+    auto scores = [&](int ks) {
 #pragma unroll
-      for (int kc = 0; kc < KC; ++kc) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kc], qf[kc], s[kb], 0, 0, 0);
-    }
-    if (need_mask) {
+      for (int kb = 2 * ks; kb < 2 * ks + 2; ++kb) {
 #pragma unroll
-      for (int kb = 0; kb < NKB; ++kb)
+        for (int qb = 0; qb < 2; ++qb) s[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
-          const bool vis = (j <= i_mine) & (!sa | (j < a.sink_lim) | (j >= w_lo_mine));
-          s[kb][r] = vis ? s[kb][r] : -INFINITY;
-        }
-    }
-    // ---- online softmax for this lane's query column.  The weights are taken against the reference m_ref
-    // the accumulators already refer to, WITHOUT looking for the block's maximum first: any reference gives
-    // the same quotient, and fp32 / bf16 keep their relative precision over the whole exponent range.  Only
-    // when a row has no reference yet, or some weight of the block left the guarded range (or overflowed),
-    // does the wave take the block's maximum, move the reference there (rescaling l and O) and redo the
-    // weights.  In the steady state the maximum, its cross-lane step and the rescale test are not executed.
-    bf16x8 pf[NKB][2];
-    float l_blk;
-    auto weights = [&](float mneg) {
+        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb)
+            s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kc], qf[qb][kc], s[kb][qb], 0, 0, 0);
+      }
+    };
+    // Softmax weights against the reference m_ref the accumulators already refer to, WITHOUT looking for the
+    // block's maximum first: any reference gives the same quotient, and fp32 / bf16 keep their relative
+    // precision over the whole exponent range.  A row without a reference yet uses 0.
+    float l_blk[2];
+    auto weights = [&]() {
       const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-      l_blk = 0.f;
 #pragma unroll
-      for (int kb = 0; kb < NKB; ++kb)
+      for (int qb = 0; qb < 2; ++qb) {
+        const float mneg = m_ref[qb] == -INFINITY ? 0.f : -m_ref[qb] * a.scale_log2;
+        l_blk[qb] = 0.f;
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
+        for (int ks = 0; ks < KS; ++ks) {
           uint32_t pk[4];
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
-            const float p0 = fast_exp2(__builtin_fmaf(s[kb][8 * c + 2 * t], a.scale_log2, mneg));
-            const float p1 = fast_exp2(__builtin_fmaf(s[kb][8 * c + 2 * t + 1], a.scale_log2, mneg));
+            const f32x4& sv = s[2 * ks + (t >> 1)][qb];
+            const float p0 = fast_exp2(__builtin_fmaf(sv[2 * (t & 1)], a.scale_log2, mneg));
+            const float p1 = fast_exp2(__builtin_fmaf(sv[2 * (t & 1) + 1], a.scale_log2, mneg));
             pk[t] = pack_bf16(p0, p1);
             // the denominator sums the same rounded weights the numerator uses
-            l_blk = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[t]), ones, l_blk, false);
+            l_blk[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[t]), ones, l_blk[qb], false);
           }
-          pf[kb][c] = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
+          pf[qb][ks] = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
         }
+      }
     };
-    bool redo = !all_ref;                                                      // some row has no reference yet
-    if (!redo) {
-      weights(-m_ref * a.scale_log2);
-      redo = __builtin_amdgcn_ballot_w64(!(l_blk < kWeightGuard)) != 0;        // also true for +inf
+    auto accumulate = [&](int ks) {        // o[db][qb][i] is d = 16*db + 4*g + i of query row (qb, n)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+          o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[ks][db], pf[qb][ks], o[db][qb], 0, 0, 0);
+    };
+
+    load_k(0);
+    load_k(1);
+    __builtin_amdgcn_sched_barrier(0);
+    scores(0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(0);
+    __builtin_amdgcn_sched_barrier(0);
+    scores(1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (need_mask) {
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int j = j0 + 16 * kb + 4 * g + i;
+            const bool vis = (j <= i_mine[qb]) & (!sa | (j < a.sink_lim) | (j >= w_lo_mine[qb]));
+            s[kb][qb][i] = vis ? s[kb][qb][i] : -INFINITY;
+          }
     }
-    if (redo) {
-      float mloc = s[0][0];
+    weights();
+    // Only when a row has no reference yet, or some weight of the block left the guarded range (or
+    // overflowed), does the wave take the block's maximum, move the reference there (rescaling l and O) and
+    // redo the weights.  In the steady state the maximum, its cross-lane steps and the rescale are not executed.
+    if (!all_ref || __builtin_amdgcn_ballot_w64(!(l_blk[0] < kWeightGuard) | !(l_blk[1] < kWeightGuard)) != 0) {
 #pragma unroll
-      for (int kb = 0; kb < NKB; ++kb)
+      for (int qb = 0; qb < 2; ++qb) {
+        float mloc = s[0][qb][0];
 #pragma unroll
-        for (int r = (kb == 0 ? 1 : 0); r < 16; ++r) mloc = fmaxf(mloc, s[kb][r]);
-      mloc = max_across_halves(mloc);
-      const float m_new = fmaxf(m_ref, mloc);
-      if (m_new > m_ref) {                                                     // false while both are -inf
-        const float al = fast_exp2((m_ref - m_new) * a.scale_log2);            // 0 for a row's first reference
-        l_run *= al;
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) o[db] *= al;
-        m_ref = m_new;
-      }
-      weights(m_ref == -INFINITY ? 0.f : -m_ref * a.scale_log2);               // a row that has seen no key yet
-      all_ref = __builtin_amdgcn_ballot_w64(m_ref == -INFINITY) == 0;
-    }
-    l_run += l_blk;
-    // ---- O^T += V^T P^T
+          for (int i = 0; i < 4; ++i) mloc = fmaxf(mloc, s[kb][qb][i]);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));                              // over the 4 lanes of the row
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float m_new = fmaxf(m_ref[qb], mloc);
+        if (m_new > m_ref[qb]) {                                               // false while both are -inf
+          const float al = fast_exp2((m_ref[qb] - m_new) * a.scale_log2);      // 0 for a row's first reference
+          l_run[qb] *= al;
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          FLUX_LDS char* vp = st + v_rd[db] + (32 * kb + 16 * c) * ROWB;
-          const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)vp);
-          const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)(vp + 8 * ROWB));
-          const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][c], o[db], 0, 0, 0);
+          for (int db = 0; db < DB; ++db) o[db][qb] *= al;
+          m_ref[qb] = m_new;
         }
       }
+      weights();
+      all_ref = __builtin_amdgcn_ballot_w64((m_ref[0] == -INFINITY) | (m_ref[1] == -INFINITY)) == 0;
+    }
+    l_run[0] += l_blk[0];
+    l_run[1] += l_blk[1];
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(1);
+    __builtin_amdgcn_sched_barrier(0);
+    accumulate(0);
+    __builtin_amdgcn_sched_barrier(0);
+    accumulate(1);
   }
 
-  // ---- normalise and store: lane (n, g) holds d = 32*db + 8*(r/4) + 4*g + (r%4) of its query row
-  const float l_tot = sum_across_halves(l_run);
-  if (r_w0 + n < n_q) {
-    const float inv = 1.0f / l_tot;
-    const int64_t off = ((int64_t)(q_begin + r_w0 + n) * a.hq + h) * D;
+  // ---- normalise and store: lane (n, g) holds d = 16*db + 4*g .. +3 of its two query rows
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+  for (int qb = 0; qb < 2; ++qb) {
+    float l_tot = l_run[qb];
+    l_tot += __shfl_xor(l_tot, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (r_w0 + 16 * qb + n < n_q) {
+      const float inv = 1.0f / l_tot;
+      const int64_t off = ((int64_t)(q_begin + r_w0 + 16 * qb + n) * a.hq + h) * D;
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        const int d = 32 * db + 8 * rr + 4 * g;
-        const float x0 = o[db][4 * rr] * inv, x1 = o[db][4 * rr + 1] * inv;
-        const float x2 = o[db][4 * rr + 2] * inv, x3 = o[db][4 * rr + 3] * inv;
+      for (int db = 0; db < DB; ++db) {
+        const int d = 16 * db + 4 * g;
+        const float x0 = o[db][qb][0] * inv, x1 = o[db][qb][1] * inv;
+        const float x2 = o[db][qb][2] * inv, x3 = o[db][qb][3] * inv;
         if (a.out_fp32) {
           *(f32x4*)((float*)a.out + off + d) = f32x4{x0, x1, x2, x3};
         } else {
           *(u32x2*)((__bf16*)a.out + off + d) = u32x2{pack_bf16(x0, x1), pack_bf16(x2, x3)};
         }
       }
+    }
   }
 }
 

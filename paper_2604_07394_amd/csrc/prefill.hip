@@ -52,9 +52,9 @@ __device__ __forceinline__ void dma16(const char* base /*uniform*/, int lane_off
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
 }
 
-template <int D, int NKB>                 // NKB: 32-key blocks per iteration (BN = 32 * NKB keys)
-__global__ __launch_bounds__(256, NKB == 1 ? 3 : 2) void prefill_kernel(PrefillArgs a) {
-  constexpr int BN = 32 * NKB;
+template <int D>
+__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
+  constexpr int BN = 64;                  // keys per iteration: two halves of 32, the K dimension of one PV MFMA
   constexpr int KC = D / 32;              // MFMA k-steps over the head dimension (QK^T)
   constexpr int DB = D / 16;              // 16-wide output blocks over the head dimension (PV)
   constexpr int KB = BN / 16;             // 16-key blocks of S^T per iteration
@@ -464,9 +464,8 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   }
   if (n_wg > 0x7FFFFFFFll) return hipErrorInvalidValue;
   const dim3 grid((unsigned)n_wg);
-  // 64 keys per iteration (NKB = 2): 32-key tiles with three workgroups per CU measured no faster
-  if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((prefill_kernel<64, 2>), grid, dim3(256), 0, s, a);
+  if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((prefill_kernel<64>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

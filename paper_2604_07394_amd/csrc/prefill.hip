@@ -61,16 +61,18 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int KS = BN / 32;             // 32-key steps of the PV product per iteration
   constexpr int CPR = D / 8;              // 16-byte chunks per row
   constexpr int ROWB = D * 2;             // bytes per K/V row
-  // K tile: rows padded by two chunks.  A wave-wide 16-byte LDS read is served in four passes of 16 lanes, and
-  // within lanes 0..31 the passes are {0-3, 12-15, 20-27} and {4-11, 16-19, 28-31} (measured with the bank
-  // conflict counter); with lane (n, g) at row n, chunk g, a pitch of 8 banks mod 64 keeps every pass on 64
-  // distinct banks, a pitch of 4 banks (one padding chunk) does not
-  constexpr int KPAD = 2;
-  constexpr int KPITCH = ROWB + 16 * KPAD;
-  constexpr int NKI = (BN * (CPR + KPAD) + 63) / 64;   // wave-wide 1 KB transfers per K tile (padding chunks included)
+  // K tile: unpadded rows, the 16-byte chunk index XOR-swizzled by the row (D = 128: row & 15; D = 64, two
+  // rows per 64 banks: (row >> 1) & 7).  A wave-wide 16-byte LDS read is served in four passes of 16 lanes,
+  // and within lanes 0..31 the passes are {0-3, 12-15, 20-27} and {4-11, 16-19, 28-31} (measured with the
+  // bank conflict counter).  With lane (n, g) reading row n, chunk 4*kc + g, a pass holds rows {0-3, 12-15}
+  // at one chunk and rows {4-11} at the chunk next to it; both row sets are closed under XOR with 1, 2 and
+  // 3, so the swizzled chunks of a pass are a permutation of all 16 and every pass covers 64 distinct banks.
+  // (Rows padded by one chunk give two-way conflicts with this mapping, by two chunks none.)
+  constexpr int KPITCH = ROWB;
+  constexpr int NKI = BN * CPR / 64;         // wave-wide 1 KB transfers per K tile
   constexpr int NVI = BN * CPR / 64;         // wave-wide 1 KB transfers per V tile
-  constexpr int KTILE = NKI * 1024;       // bytes (whole transfers; the tail of the last one is unused)
-  constexpr int VTILE = BN * ROWB;        // V tile: unpadded rows, chunk index XOR-swizzled by the row
+  constexpr int KTILE = BN * ROWB;
+  constexpr int VTILE = BN * ROWB;        // V tile: unpadded rows, 32-byte units XOR-swizzled by the row
   constexpr int STAGE = KTILE + VTILE;
   constexpr int KPW = (NKI + 3) / 4;         // K transfers per wave (the last may be missing)
   constexpr int VPW = (NVI + 3) / 4;         // V transfers per wave
@@ -183,14 +185,12 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   // ---- direct global -> LDS transfers.  One transfer moves 64 x 16 bytes to 1 KB of consecutive LDS;
   // which (row, chunk) a lane fetches decides where that chunk lands.  Per lane, the row and chunk of
   // each of this wave's transfers are fixed for the whole kernel.
-  // K: LDS slot p = 64*I + l of transfer I holds (row p/(CPR+KPAD), chunk p%(CPR+KPAD)); the padding slots of a
-  // row re-fetch its last chunk.  V: transfer I covers rows I*RPI .. +RPI-1; lane l sits at
-  // (row l/CPR, physical chunk l%CPR) and fetches the logical chunk that the swizzle maps there.
-  auto k_slot = [&](int t, int rmax) {
-    const int p = 64 * (w + 4 * t) + l;
-    return min(min(p / (CPR + KPAD), BN - 1), rmax) * pitch_g + min(p % (CPR + KPAD), CPR - 1) * 16;
-  };
+  // Transfer I covers rows I*RPI .. +RPI-1 of a tile; lane l sits at (row l/CPR, physical chunk l%CPR) and
+  // fetches the logical chunk that the swizzle maps there.  For K the swizzle of row (w + 4t)*RPI + l/CPR
+  // is (4w + l/16) & (CPR-1) for both head sizes, a per-lane constant.
   const int v_lrow = l / CPR;
+  const int k_chunk = (l % CPR) ^ ((4 * w + (l >> 4)) & (CPR - 1));
+  auto k_slot = [&](int t, int rmax) { return min((w + 4 * t) * RPI + v_lrow, rmax) * pitch_g + k_chunk * 16; };
   // the 32-byte units of a V row are XOR-swizzled by the row (D = 128: row & 7; D = 64, two rows per 64
   // banks: (row >> 1) & 3), which makes the transposing reads below conflict-free; the row of transfer
   // w + 4t, lane l is (w + 4t) * RPI + l / CPR, so the swizzle is a per-lane constant
@@ -230,7 +230,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   };
 
   // ---- per-lane LDS read offsets (bytes, relative to the stage)
-  const int k_rd = n * KPITCH + g * 16;                       // K fragment: row 16*kb + n, d = 32*kc + 8*g ..
+  // K fragment (kb, kc): row 16*kb + n, logical chunk 4*kc + g (d = 32*kc + 8*g ..), swizzled by the row
+  const int k_xr = D == 128 ? n : (n >> 1);
+  int k_rd[KC];
+#pragma unroll
+  for (int kc = 0; kc < KC; ++kc) k_rd[kc] = n * KPITCH + (((4 * kc + g) ^ k_xr) * 16);
   // V^T fragment for output block db: the transposing read of lane (n, g) addresses row 4*g + n/4, columns
   // 16*db + 4*(n%4) .. +3, and returns V^T[16*db + n][keys 4g .. 4g+3] of the 16-row group
   const int v_row = 4 * g + (n >> 2);
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
       for (int kb = 2 * ks; kb < 2 * ks + 2; ++kb)
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) kf[kb][kc] = *(FLUX_LDS bf16x8*)(st + k_rd + 16 * kb * KPITCH + 64 * kc);
+        for (int kc = 0; kc < KC; ++kc) kf[kb][kc] = *(FLUX_LDS bf16x8*)(st + k_rd[kc] + 16 * kb * KPITCH);
     };
     auto load_v = [&](int ks) {
 #pragma unroll

@@ -561,3 +561,36 @@ def test_inconsistent_lengths_are_clamped_and_flagged(F, ctx):
     H.assert_close(outp[:50].cpu().numpy(), ref, "prefill with more queries than cached positions")
     assert torch.isnan(outp[50:]).all()
     assert F.flux_last_device_status(ctx) & F.FLUX_DEV_BAD_LENGTH
+
+
+def test_workspace_sizing_for_decode(F):
+    """A context made with the size flux_workspace_needed reports runs the decode it was sized for; one made
+    with a smaller workspace refuses it with FLUX_EWORKSPACE before anything is launched."""
+    hq, hkv, d, batch, n = 16, 8, 128, 12, 900
+    cfg = F.attn_cfg(hq, hkv, d, 8, 64, 0.0, 1)
+    need = F.flux_workspace_needed(cfg, batch, n)
+    assert need > 0
+    cache = F.KVCache.empty(batch, hkv, n, d)
+    cache.kv_len.fill_(n)
+    cache.k.normal_()
+    cache.v.normal_()
+    q = torch.randn(batch, hq, d, device="cuda").to(torch.bfloat16)
+    mode = torch.ones(batch, dtype=torch.uint8, device="cuda")
+    outs = []
+    for size in (need, 0):
+        c = F.flux_create(0, size)
+        out = torch.full((batch, hq, d), float("nan"), dtype=torch.float32, device="cuda")
+        F.flux_attn_decode(c, cfg, q, n, cache, mode, out)
+        torch.cuda.synchronize()
+        assert torch.isfinite(out).all()
+        outs.append(out)
+        F.flux_destroy(c)
+    assert torch.equal(outs[0], outs[1])
+    small = F.flux_create(0, 1)                                       # rounded up to the smallest context
+    out = torch.full((batch, hq, d), float("nan"), dtype=torch.float32, device="cuda")
+    with pytest.raises(F.FluxError) as e:
+        F.flux_attn_decode(small, cfg, q, n, cache, mode, out)
+    assert e.value.code == F.FLUX_EWORKSPACE
+    torch.cuda.synchronize()
+    assert torch.isnan(out).all()                                     # nothing was launched
+    F.flux_destroy(small)

@@ -299,13 +299,14 @@ def test_decode_ragged_multi_chunk(F, ctx, d, hq, hkv):
             H.assert_close(got[b], ref[b], f"decode step {step} seq {b} (len {lay.lens[b]})")
 
 
-def test_decode_wide_ragged_batch_more_sequences_than_lanes(F, ctx):
-    """70 sequences (the device-side split walks the batch 64 at a time) with lengths from 0 to a few
-    thousand and alternating modes: every sequence is found by the prefix sum and merged with its own chunks."""
-    B, hq, hkv, d = 70, 4, 1, 128
+@pytest.mark.parametrize("B,top", [(70, 2600), (300, 600)])
+def test_decode_wide_ragged_batch_more_sequences_than_lanes(F, ctx, B, top):
+    """70 and 300 sequences (the device-side split walks the batch 64 at a time) with lengths from 0 to `top`
+    and alternating modes: every sequence is found by the prefix sum and merged with its own chunks."""
+    hq, hkv, d = 4, 1, 128
     rng = np.random.default_rng(5)
-    lens = [int(x) for x in rng.integers(0, 2600, size=B)]
-    lens[3], lens[64], lens[69] = 0, 2599, 1
+    lens = [int(x) for x in rng.integers(0, top, size=B)]
+    lens[3], lens[64], lens[B - 1] = 0, top - 1, 1
     modes = [FA if (b * 7) % 3 else SA for b in range(B)]
     lay = Layer(F, ctx, 35, B, hq, hkv, d, 2700, 16, 200)
     _, kb, vb = lay.new_tokens(lens)

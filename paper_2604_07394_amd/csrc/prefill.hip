@@ -262,12 +262,13 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     const int j0 = (it < n_a ? it : win0 + (it - n_a)) * BN;
     // does this wave see anything in the block, and does it need the element mask?
     bool skip = !wave_active || j0 > i_w_max;
-    bool need_mask = j0 + BN - 1 > i_w_min;
+    const bool mask_causal = j0 + BN - 1 > i_w_min;          // the diagonal crosses the block
+    bool mask_edge = false;                                  // a window or sink edge falls inside the block
     if (sa) {
       const bool all_sink = j0 + BN <= a.sink_lim;
       if (!all_sink) {
         if (j0 >= a.sink_lim && j0 + BN - 1 < w_lo_first) skip = true;            // before every window
-        if (j0 < w_lo_last) need_mask = true;                                     // a window edge falls inside
+        mask_edge = j0 < w_lo_last;
       }
     }
     if (skip) continue;
@@ -351,17 +352,30 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     __builtin_amdgcn_sched_barrier(0);
     scores(1);
     __builtin_amdgcn_sched_barrier(0);
-    if (need_mask) {
+    // Element masks, only on blocks an edge of the visible set crosses.  Key j = j0 + 4*g + c with the constant
+    // c = 16*kb + i, so each bound is moved into the lane once (bound - j0 - 4*g) and compared with constants.
+    if (mask_edge) {
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
+      for (int qb = 0; qb < 2; ++qb) {
+        const int hi = i_mine[qb] - j0 - 4 * g, lo = w_lo_mine[qb] - j0 - 4 * g, sl = a.sink_lim - j0 - 4 * g;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const int j = j0 + 16 * kb + 4 * g + i;
-            const bool vis = (j <= i_mine[qb]) & (!sa | (j < a.sink_lim) | (j >= w_lo_mine[qb]));
+            const int c = 16 * kb + i;
+            const bool vis = (c <= hi) & ((c < sl) | (c >= lo));
             s[kb][qb][i] = vis ? s[kb][qb][i] : -INFINITY;
           }
+      }
+    } else if (mask_causal) {
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        const int hi = i_mine[qb] - j0 - 4 * g;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s[kb][qb][i] = 16 * kb + i <= hi ? s[kb][qb][i] : -INFINITY;
+      }
     }
     weights();
     // Only when a row has no reference yet, or some weight of the block left the guarded range (or

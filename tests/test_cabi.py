@@ -47,6 +47,12 @@ def test_workspace_needed_is_host_arithmetic(F):
     assert 0 < small < big < (1 << 30)
     assert F.flux_workspace_needed(F.attn_cfg(32, 5, 128, 0, 1), 1, 100) == 0       # bad head ratio
     assert F.flux_workspace_needed(cfg, 0, 100) == 0
+    # split-K partials: at most 1024 + (sequence, KV head) pairs units of group x (D + 2) floats whatever the
+    # lengths, fewer when even the longest list has few 256-key chunks
+    fixed = F.flux_workspace_needed(cfg, 1, 1) - 8 * 1 * 4 * 130 * 4
+    assert big - fixed == (1024 + 8 * 8) * 4 * 130 * 4
+    assert F.flux_workspace_needed(cfg, 8, 1 << 22) == big              # no growth with the length
+    assert small - fixed == 8 * 16 * 4 * 130 * 4                         # 8 pairs x 16 chunks of 256 keys
 
 
 @pytest.fixture()

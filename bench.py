@@ -161,6 +161,8 @@ def main():
             "speedup_mix_vs_all_fa": t_fa / t_mix if t_fa else None, "predicted_speedup_from_flops": pred,
             "omega_msr": float((mask_mix == 0).mean()),
             "mask": args.mask, "fa_kernel_ms": fa_avg, "sa_kernel_ms": sa_avg,
+            "fa_kernel_ms_median": float(np.median(fa_ms)) if fa_ms else None,
+            "sa_kernel_ms_median": float(np.median(sa_ms)) if sa_ms else None,
             "sa_kernel_tflops": flops_sa / (sa_avg * 1e-3) / 1e12 if sa_ms else None,
         }
         achieved = flops_fa / (fa_avg * 1e-3) / 1e12 if fa_ms else 0.0
@@ -350,6 +352,8 @@ def main():
             "speedup_mix_vs_all_fa": td_fa / td_mix if td_fa else None,
             "predicted_speedup_from_bytes": (LD * bytes_fa) / (n_fa * bytes_fa + (LD - n_fa) * bytes_sa),
             "fa_layer_ms": fa_avg, "sa_layer_ms": sa_avg,
+            "fa_layer_ms_median": float(np.median(fa_ms)) if fa_ms else None,
+            "sa_layer_ms_median": float(np.median(sa_ms)) if sa_ms else None,
             "roofline": {"kernel": "decode_splitk_kernel<128, true> + decode_combine_kernel<128> (FA layers)",
                          "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": ach / PEAK_HBM_GBS,

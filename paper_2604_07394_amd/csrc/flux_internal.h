@@ -45,8 +45,12 @@ inline SaGeom sa_geom(const flux_attn_cfg& cfg) {
   while ((1 << sh) < b) ++sh;
   SaGeom g;
   g.shift = sh;
-  g.sink_lim = ((cfg.n_sink + b - 1) >> sh) << sh;
-  g.win_blocks = (cfg.window + b - 1) >> sh;
+  // rounded up in 64 bits and cut at the largest int: n_sink or window near INT32_MAX ("SA sees everything",
+  // Eq. 2 degenerating to Eq. 1) must not wrap.  Positions are below INT32_MAX, so the cut changes nothing.
+  const long long sink_lim = (((long long)cfg.n_sink + b - 1) >> sh) << sh;
+  const long long win_blocks = ((long long)cfg.window + b - 1) >> sh;
+  g.sink_lim = sink_lim > 0x7FFFFFFFll ? 0x7FFFFFFF : (int)sink_lim;
+  g.win_blocks = win_blocks > (0x7FFFFFFFll >> sh) ? (0x7FFFFFFF >> sh) : (int)win_blocks;
   return g;
 }
 __device__ __forceinline__ int window_start(int i, int shift, int win_blocks) {

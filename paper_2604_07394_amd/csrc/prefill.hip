@@ -47,9 +47,9 @@ constexpr float kWeightGuard = 1073741824.0f;   // 2^30: a block whose weights s
 // One wave-wide direct global -> LDS transfer: every lane fetches its own 16 bytes, the 64 pieces land
 // at lds_base + 16 * lane.  Issued as inline assembly so that the compiler does not serialise later LDS
 // reads of the OTHER stage behind it; completion is awaited explicitly with vmcnt(0) before the barrier.
-// M0 (the LDS base of the transfer) is written here and holds no other live value in these kernels.
+// M0 (the LDS base of the transfer) is written here and declared as clobbered.
 __device__ __forceinline__ void dma16(const char* base /*uniform*/, int lane_off, uint32_t lds_base /*uniform*/) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
 
 template <int D>

@@ -156,3 +156,18 @@ def test_block_size_validation(F, nodev):
     call = lambda blk: rc_of(F, F.flux_attn_decode, nodev, F.attn_cfg(8, 2, 128, 4, 16, 0.0, 0, blk), 4096, 32, kc, 512, 1024)
     assert call(0) == F.FLUX_EHIP and call(1) == F.FLUX_EHIP and call(64) == F.FLUX_EHIP
     assert call(48) == F.FLUX_EINVAL and call(-64) == F.FLUX_EINVAL and call(1 << 17) == F.FLUX_EINVAL
+
+
+def test_window_and_sinks_near_the_largest_int_do_not_wrap(F, nodev):
+    """'SA sees everything' (Eq. 2 degenerating to Eq. 1) is naturally written as window = INT32_MAX.  With a
+    block size above one the window is rounded up to whole blocks; that rounding must not wrap: a ring cache
+    can never hold such a window (FLUX_ECAPACITY, not a negative row count that passes), and the plain calls
+    stay valid."""
+    big = (1 << 31) - 1
+    kc = cache_struct(F)
+    for blk in (0, 64, 65536):
+        assert rc_of(F, F.flux_attn_decode, nodev, F.attn_cfg(8, 2, 128, 4, big, 0.0, 0, blk), 4096, 32, kc, 512, 1024) == F.FLUX_EHIP
+        assert rc_of(F, F.flux_attn_decode, nodev, F.attn_cfg(8, 2, 128, big, 16, 0.0, 0, blk), 4096, 32, kc, 512, 1024) == F.FLUX_EHIP
+        assert rc_of(F, F.flux_attn_decode_ring, nodev, F.attn_cfg(8, 2, 128, 4, big, 0.0, 0, blk), 4096, kc, 1024) == F.FLUX_ECAPACITY
+        assert rc_of(F, F.flux_attn_decode_ring, nodev, F.attn_cfg(8, 2, 128, big, 16, 0.0, 0, blk), 4096, kc, 1024) == F.FLUX_ECAPACITY
+        assert F.flux_workspace_needed(F.attn_cfg(8, 2, 128, big, big, 0.0, 0, blk), 2, 4096) > 0

@@ -140,24 +140,33 @@ def test_long_context_decode_shape_one_layer(F, G, ctx):
     G.fill_normal_bf16(vd, SEED, synth.stream_id(synth.STREAM_VDEC))
     F.flux_kv_append(ctx, cache, HKV, D, kd[0, 0], vd[0, 0], i32(list(range(B + 1))), B, 1)
     cfg = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 1)
-    out = {}
+    cfg16 = F.attn_cfg(HQ, HKV, D, NS, W, 0.0, 0)              # bench.py's output type (BF16 throughout, App. B.3)
+    out, out16 = {}, {}
     for mode, bound in ((FA, N + 1), (SA, NS + W)):
         o = torch.full((B, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
         F.flux_attn_decode(ctx, cfg, qd[0, 0], bound, cache, u8([mode] * B), o)
         out[mode] = o
+        o16 = torch.full((B, HQ, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        F.flux_attn_decode(ctx, cfg16, qd[0, 0], bound, cache, u8([mode] * B), o16)
+        out16[mode] = o16
     torch.cuda.synchronize()
+    for mode in (FA, SA):                                       # the bf16 output is the fp32 output rounded once
+        assert torch.equal(out16[mode], out[mode].to(torch.bfloat16))
     assert kv_len.cpu().tolist() == [N + 1] * B
     # the appended row landed at position N of every (sequence, KV head)
     assert torch.equal(kc[:, :, N].reshape(B * HKV, D), kd[0, 0]) and torch.equal(vc[:, :, N].reshape(B * HKV, D), vd[0, 0])
     q = qd[0, 0].view(B, HQ, D)
     g = HQ // HKV
-    for b, kvh in ((0, 0), (3, 5), (7, 7), (5, 2)):
+    # every sequence on one KV head, every KV head once, plus four more pairs
+    for b, kvh in ((0, 0), (1, 3), (2, 6), (3, 5), (4, 1), (5, 2), (6, 4), (7, 7), (0, 7), (7, 0), (3, 2), (4, 4)):
         kf = H.torch_to_f64(kc[b, kvh, :N + 1])
         vf = H.torch_to_f64(vc[b, kvh, :N + 1])
         for mode in (FA, SA):
             ref = O.attention_row(H.torch_to_f64(q[b, kvh * g:(kvh + 1) * g]), kf, vf, N, mode, NS, W)
             got = H.torch_to_f64(out[mode][b, kvh * g:(kvh + 1) * g])
             e = H.assert_close(got, ref, f"long decode seq {b} kv head {kvh} mode {mode}")
+            got16 = H.torch_to_f64(out16[mode][b, kvh * g:(kvh + 1) * g])
+            assert (np.abs(got16 - ref) <= np.maximum(1e-2, 2.0 ** -8 * np.abs(ref))).all()
             print("long decode", b, kvh, mode, "max-abs %.2e rel-L2 %.2e" % e)
     assert F.flux_last_device_status(ctx) == 0
 
@@ -176,11 +185,14 @@ def test_long_context_decode_shape_one_layer(F, G, ctx):
     o_full = torch.full((B, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
     F.flux_attn_decode_ring(ctx, cfg, qd[0, 0], ring, o_ring)
     F.flux_attn_decode(ctx, cfg, qd[0, 0], NS + W, cache, u8([SA] * B), o_full)
+    o_ring16 = torch.full((B, HQ, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    F.flux_attn_decode_ring(ctx, cfg16, qd[0, 0], ring, o_ring16)
     torch.cuda.synchronize()
     assert ring.kv_len.cpu().tolist() == [N + 2] * B
     assert torch.equal(o_ring, o_full)
+    assert torch.equal(o_ring16, o_ring.to(torch.bfloat16))
     q = qd[0, 0].view(B, HQ, D)
-    for b, kvh in ((1, 4), (6, 0)):
+    for b, kvh in ((1, 4), (6, 0), (0, 2), (7, 6)):
         kf = H.torch_to_f64(kc[b, kvh, :N + 2])
         vf = H.torch_to_f64(vc[b, kvh, :N + 2])
         ref = O.attention_row(H.torch_to_f64(q[b, kvh * g:(kvh + 1) * g]), kf, vf, N + 1, SA, NS, W)
@@ -252,7 +264,7 @@ def test_end_to_end_routed_ragged_batch(F, G, ctx):
     # ---- router against the oracle
     x2d = q[0].view(T, hidden)
     w1f, w2f = H.torch_to_f64(w1[0, 0]), H.torch_to_f64(w2[0, 0])
-    ref_modes = []
+    ref_modes, margins = [], []
     for b in range(B):
         s, n = int(starts[b]), lens[b]
         # only the rows the oracle's pooling selects are copied back; over them its mean takes every row
@@ -261,11 +273,13 @@ def test_end_to_end_routed_ragged_batch(F, G, ctx):
         ref_logits, ref_mode = O.router(H.torch_to_f64(rows), 0, w1f, None, w2f, None)
         got = logits[b].cpu().numpy().astype(np.float64)
         assert np.abs(got - ref_logits).max() < 1e-6, (b, got, ref_logits)
-        if abs(ref_logits[0] - ref_logits[1]) >= 1e-6:
-            assert int(mode[b]) == ref_mode
-        ref_modes.append(int(mode[b]))
-    print("routed modes", ref_modes, "logits", logits.cpu().numpy().round(5).tolist())
-    assert set(ref_modes) <= {FA, SA}
+        margins.append(abs(ref_logits[0] - ref_logits[1]))
+        ref_modes.append(int(ref_mode))
+    # the decision contract: bit-exact wherever the oracle's margin is at least 1e-6; a seed with a smaller
+    # margin anywhere is a bad seed, not a kernel failure, and must be replaced
+    print("routed modes", ref_modes, "min margin %.3e" % min(margins), "logits", logits.cpu().numpy().round(5).tolist())
+    assert min(margins) >= 1e-6, f"seed {SEED}: a router margin below 1e-6, pick another seed"
+    assert mode.cpu().tolist() == ref_modes
 
     # ---- prefill rows under the routed mask, and the other mode for the longest sequence
     g = HQ // HKV
@@ -299,7 +313,7 @@ def test_end_to_end_routed_ragged_batch(F, G, ctx):
         F.flux_attn_decode(ctx, cfg, qd[0, 0], max(lens) + step + 1, cache, mode, od)
         torch.cuda.synchronize()
         qv = qd[0, 0].view(B, HQ, D)
-        for b, kvh in ((0, 2), (3, 5)):
+        for b, kvh in ((0, 2), (1, 7), (2, 0), (3, 5)):       # every sequence of the mixed-mode launch
             n = lens[b] + step + 1
             kf = H.torch_to_f64(cache.k[b, kvh, :n])
             vf = H.torch_to_f64(cache.v[b, kvh, :n])

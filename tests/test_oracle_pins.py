@@ -50,6 +50,22 @@ def test_visible_pair_totals_config_shapes():
         total_fa += int(O.visible(i, j, FA, 128, 4096).sum())
     assert total_sa == 129_493_056
     assert total_fa == 536_887_296
+    # High-sparsity config: S 65536, 64 sinks, window 2048.  The predicate is evaluated on two disjoint key
+    # slices per block of 1024 rows: the sinks below the slice, and everything from `window` keys before the
+    # block's first row to its last row (no other key can be visible to a row of the block); sampled whole
+    # rows below check that nothing outside the slices is.
+    n, n_sink, window = 65536, 64, 2048
+    total_sa = 0
+    for r0 in range(0, n, 1024):
+        i = np.arange(r0, r0 + 1024)[:, None]
+        lo = max(0, r0 - window)
+        total_sa += int(O.visible(i, np.arange(lo, r0 + 1024)[None, :], SA, n_sink, window).sum())
+        total_sa += int(O.visible(i, np.arange(0, min(n_sink, lo))[None, :], SA, n_sink, window).sum())
+    for i in (0, 63, 64, 2047, 2048, 2111, 2112, 40000, 65535):   # whole rows against the closed form
+        assert int(O.visible(i, np.arange(n), SA, n_sink, window).sum()) == closed_form_visible(i, n_sink, window)
+    assert total_sa == 136_182_816
+    assert n * (n + 1) // 2 == 2_147_516_416
+    assert int(O.visible(np.arange(n - 64, n)[:, None], np.arange(n)[None, :], FA, n_sink, window).sum()) == sum(range(n - 63, n + 1))
 
 
 def test_query_rows_are_the_last_positions():

@@ -151,6 +151,23 @@ int flux_attn_prefill(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, co
 int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int max_kv_len,
                      const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream);
 
+/* flux_attn_decode for callers that cannot allocate device memory at all (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): no context, and no hipMalloc / hipFree / allocating library
+ * call inside.  The split-K partial results go to a static device array of FLUX_STATIC_SCRATCH_BYTES that
+ * every GPU the library runs on holds until the process ends; the call works on the CURRENT device, whose
+ * copy of the array is looked up once (at flux_create on that device, else at the first call).
+ * Same arguments, kernels and results (bit for bit) as flux_attn_decode, plus
+ *   status: dev uint32 (4-byte aligned), caller-owned, or NULL.  The FLUX_DEV_* bits of this call are OR-ed
+ *           into it (sticky; the caller reads and clears it); with NULL they go to a word nobody reads.
+ * A shape whose partials exceed the array gives FLUX_EWORKSPACE: the partials take
+ * min(1024 + pairs, pairs * ceil(max_kv_len / 256)) * min(group, 16) * (head_dim + 2) * 4 bytes with
+ * pairs = batch * n_kv_heads * ceil(group / 16), group = n_q_heads / n_kv_heads (2.3 MB for batch 8, 32/8
+ * heads of 128 at any length).  All calls on one GPU share that GPU's array: calls that overlap on one GPU
+ * (two streams, two threads) race and must be ordered by the caller.  Nothing needs clearing between calls. */
+#define FLUX_STATIC_SCRATCH_BYTES ((size_t)16 * 1024 * 1024 + 256)
+int flux_attn_decode_static(const flux_attn_cfg* cfg, const void* q, int max_kv_len, const flux_kv_cache* cache,
+                            const uint8_t* mode, void* out, uint32_t* status, void* stream);
+
 /* ---- Sparse-decode residency (Sec. 3.3 "Efficient Deployment": a sparse layer keeps only the minimal
  * KV cache its kernel needs and never stores the rest of the history; retrieval layers keep everything).
  *

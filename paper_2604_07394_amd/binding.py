@@ -26,7 +26,8 @@ FA, SA = 1, 0
 
 EXPORTS = ["flux_create", "flux_destroy", "flux_strerror", "flux_workspace_needed", "flux_last_device_status",
            "flux_router", "flux_kv_append", "flux_attn_prefill", "flux_attn_decode",
-           "flux_kv_append_ring", "flux_kv_compact_ring", "flux_attn_decode_ring"]
+           "flux_kv_append_ring", "flux_kv_compact_ring", "flux_attn_decode_ring", "flux_attn_decode_static"]
+STATIC_SCRATCH_BYTES = 16 * 1024 * 1024 + 256
 
 
 class FluxAttnCfg(C.Structure):
@@ -63,6 +64,9 @@ _lib.flux_attn_prefill.restype = C.c_int
 _lib.flux_attn_decode.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_int, C.POINTER(FluxKVCache),
                                   C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.flux_attn_decode.restype = C.c_int
+_lib.flux_attn_decode_static.argtypes = [C.POINTER(FluxAttnCfg), C.c_void_p, C.c_int, C.POINTER(FluxKVCache), C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.flux_attn_decode_static.restype = C.c_int
 _lib.flux_kv_append_ring.argtypes = [C.c_void_p, C.POINTER(FluxKVCache), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
 _lib.flux_kv_append_ring.restype = C.c_int
@@ -178,6 +182,12 @@ def flux_attn_decode(ctx, cfg, q, max_kv_len, cache, mode, out, stream=None) -> 
     cs = _cache_struct(cache)
     _check(_lib.flux_attn_decode(ctx, C.byref(cfg), _ptr(q), max_kv_len, C.byref(cs), _ptr(mode), _ptr(out),
                                  _stream(stream)))
+
+
+def flux_attn_decode_static(cfg, q, max_kv_len, cache, mode, out, status=None, stream=None) -> None:
+    cs = _cache_struct(cache)
+    _check(_lib.flux_attn_decode_static(C.byref(cfg), _ptr(q), max_kv_len, C.byref(cs), _ptr(mode), _ptr(out),
+                                        _ptr(status), _stream(stream)))
 
 
 def flux_kv_append_ring(ctx, ring, n_kv_heads, head_dim, n_sink, window, k_new, v_new, cu_new, total_new, max_new,

@@ -5,11 +5,18 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "flux_internal.h"
 
 using namespace flux;
+
+// Scratch of flux_attn_decode_static, the entry point for callers that cannot allocate: a sticky status word
+// (first 256 bytes) and the split-K partial results.  Every GPU the library runs on holds its own copy of the
+// array, at its own address, until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress: kernels and copies are given the address that call returns, never the name.
+static __device__ __align__(256) unsigned char scratch[FLUX_STATIC_SCRATCH_BYTES];
 
 struct flux_ctx {
   Ctx c;
@@ -25,6 +32,30 @@ int hip_fail(hipError_t e) {
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+constexpr size_t kStaticHeader = 256;      // status word of the static scratch; the partials follow
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, resolved once per device
+
+// Address of the CURRENT device's copy of `scratch` (resolved at the first use on that device; no allocation
+// and no stream work).  The array is zero when the module is loaded, which is all the status word needs.
+hipError_t static_scratch(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = (char*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 int check_cfg(const flux_attn_cfg* cfg) {
   if (!cfg) return FLUX_EINVAL;
@@ -102,6 +133,15 @@ int flux_create(flux_ctx** out, int device, size_t workspace_bytes) {
   ctx->c.small = (float*)(ctx->c.ws + kHeaderBytes);
   ctx->c.partials = (float*)(ctx->c.ws + kHeaderBytes + kSmallBytes);
   ctx->c.partials_bytes = workspace_bytes - kHeaderBytes - kSmallBytes;
+  // set-up on this device also resolves the static scratch of flux_attn_decode_static, so that a caller who
+  // created a context first never takes that step inside a region where it would be unwelcome
+  char* unused = nullptr;
+  e = static_scratch(&unused);
+  if (e != hipSuccess) {
+    (void)hipFree(ctx->c.ws);
+    delete ctx;
+    return hip_fail(e);
+  }
   *out = ctx;
   return FLUX_OK;
 }
@@ -195,6 +235,34 @@ int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int
   if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
   const hipError_t e = launch_decode(ctx->c, *cfg, q, max_kv_len, *cache, mode, 0, out, (hipStream_t)stream);
+  return e == hipSuccess ? FLUX_OK : hip_fail(e);
+}
+
+int flux_attn_decode_static(const flux_attn_cfg* cfg, const void* q, int max_kv_len, const flux_kv_cache* cache,
+                            const uint8_t* mode, void* out, uint32_t* status, void* stream) {
+  if (!q || !mode || !out) return FLUX_EINVAL;
+  int rc = check_cfg(cfg);
+  if (rc != FLUX_OK) return rc;
+  rc = check_cache(cache, cfg->head_dim);
+  if (rc != FLUX_OK) return rc;
+  if (max_kv_len < 0) return FLUX_EINVAL;
+  if (max_kv_len > cache->capacity) return FLUX_ECAPACITY;
+  if (!aligned16(q) || !aligned16(out) || ((uintptr_t)status & 3u)) return FLUX_EINVAL;
+  const DecodePlan p = plan_decode(*cfg, cache->batch, max_kv_len);
+  if (decode_partials_bytes(*cfg, p) > FLUX_STATIC_SCRATCH_BYTES - kStaticHeader) return FLUX_EWORKSPACE;
+  char* base = nullptr;
+  const hipError_t es = static_scratch(&base);
+  if (es != hipSuccess) return hip_fail(es);
+  // A context on the stack that owns nothing: the kernels take the scratch address as they take the
+  // workspace of a flux_create context.  Nothing has to be cleared between calls: the merge kernel reads
+  // only partial rows that the split-K kernel of the same call has written, and the status word is sticky.
+  Ctx c;
+  memset(&c, 0, sizeof(c));
+  c.device = 0;
+  c.status = status ? status : (uint32_t*)base;
+  c.partials = (float*)(base + kStaticHeader);
+  c.partials_bytes = FLUX_STATIC_SCRATCH_BYTES - kStaticHeader;
+  const hipError_t e = launch_decode(c, *cfg, q, max_kv_len, *cache, mode, 0, out, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
 }
 

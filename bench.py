@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+CSRC = os.path.join(ROOT, "paper_2604_07394_amd", "csrc")
 
 
 def parse():
@@ -30,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--decode-steps", type=int, default=50)
+    ap.add_argument("--decode-steps", type=int, default=128)
     ap.add_argument("--decode-warmup", type=int, default=10)
     ap.add_argument("--only", choices=["all", "prefill", "decode", "router"], default="all",
                     help="restrict the run (profiling); the JSON line then carries nulls for the rest")
@@ -41,22 +42,42 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="also time one FA and one SA layer at context lengths 8K..256K (prefill and decode, batch 1)")
     ap.add_argument("--extra", action="store_true",
-                    help="also time the high-sparsity prefill workload (28 layers, batch 2, 65536 tokens, 28/4 heads, "
-                         "21 SA layers) and the end-to-end routed workload (32 layers, ragged batch 8K/32K/64K/128K, "
-                         "router decisions taken on the device)")
+                    help="more repetitions of the high-sparsity prefill workload (28 layers, batch 2, 65536 tokens, 28/4 "
+                         "heads, 21 SA layers) and of the end-to-end routed workload (32 layers, ragged batch "
+                         "8K/32K/64K/128K, router decisions taken on the device); both run by default with few repetitions")
+    ap.add_argument("--no-extra", action="store_true", help="skip those two workloads")
     return ap.parse_args()
 
 
-def measured_traffic(key):
-    """HBM bytes per launch recorded under profiles/ from rocprofv3 counter runs (None if absent)."""
+def source_digest(names):
+    """sha256 over the kernel sources a counter measurement belongs to (first 16 hex digits)."""
+    import hashlib
+    h = hashlib.sha256()
+    for n in names:
+        with open(os.path.join(CSRC, n), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(key, sources):
+    """HBM bytes per launch recorded under profiles/ from rocprofv3 counter runs.  A record carries the digest
+    of the kernel sources it was measured on; it is reported only while those sources are unchanged, so a
+    later kernel change cannot leave a stale figure in the line.  Returns (bytes or None, note)."""
     try:
         for line in open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")):
             f = line.split()
-            if len(f) == 5 and f[0] == key:
-                return float(f[2]) + float(f[4])
+            if len(f) == 7 and f[0] == key:
+                if f[6] != source_digest(sources):
+                    return None, "the recorded counters were taken on other kernel sources (digest %s)" % f[6]
+                return float(f[2]) + float(f[4]), "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, see profiles/"
     except OSError:
         pass
-    return None
+    return None, "no counter record for this workload"
+
+
+def bf16_to_f64(t):
+    """torch bf16 tensor -> float64 NumPy array, exactly (inputs for the CPU baseline leg)."""
+    return t.detach().to("cpu", dtype=__import__("torch").float32).numpy().astype("float64")
 
 
 def main():
@@ -168,14 +189,17 @@ def main():
         achieved = flops_fa / (fa_avg * 1e-3) / 1e12 if fa_ms else 0.0
         roofline = {"kernel": "prefill_kernel<128> (FA layers)", "bound": "mfma", "achieved": achieved,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                    "traffic": measured_traffic("prefill_fa_stack_prefill_32768") if not args.small else None,
-                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
-                    "flops_per_launch": flops_fa, "launch_ms": fa_avg}
+                    "traffic": None, "traffic_note": "not the profiled workload",
+                    "traffic_unit": "bytes per launch",
+                    "flops_per_launch": flops_fa, "launch_ms": fa_avg,
+                    "launch_ms_source": "HIP events on the launch stream around every FA launch of the timed steps"}
+        if not args.small:
+            roofline["traffic"], roofline["traffic_note"] = measured_traffic(
+                "prefill_fa_stack_prefill_32768", ["prefill.hip", "flux_internal.h"])
 
         # ---- CPU oracle on a bounded sample of the same workload (rank 0, N = 1)
         if not args.no_cpu_baseline:
             from oracle import flux_oracle as O
-            from tests import helpers as H
             try:
                 from threadpoolctl import threadpool_info
                 cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -187,9 +211,9 @@ def main():
             budget = 1.0 if args.small else 9.0                 # seconds of oracle time per mode
             for m in (1, 0):
                 layer = int(np.nonzero(mask_mix == m)[0][0])
-                kf = H.torch_to_f64(kn[layer][:, 0])             # KV head 0 of that layer, [S, D]
-                vf = H.torch_to_f64(vn[layer][:, 0])
-                qf = H.torch_to_f64(q[layer][:, :G])             # its G query heads, [S, G, D]
+                kf = bf16_to_f64(kn[layer][:, 0])                # KV head 0 of that layer, [S, D]
+                vf = bf16_to_f64(vn[layer][:, 0])
+                qf = bf16_to_f64(q[layer][:, :G])                # its G query heads, [S, G, D]
                 rows = rng.integers(0, S, size=100000)
                 t0 = time.perf_counter()
                 done = 0
@@ -207,6 +231,36 @@ def main():
                                       "positions of one KV group (%d heads) in one FA and one SA layer, %.1f s of CPU "
                                       "work, extrapolated to %d layers x %d positions x %d groups"
                                       % (n_rows[1], n_rows[0], G, t_used, L, S, HKV)}
+
+            # ---- the Tiny configuration through the oracle IN FULL (nothing extrapolated): 4 layers [FA, SA, FA,
+            # SA], 512 tokens, 8/2 heads, D 64, 16 sinks + 128 window, prefill then 16 decode steps; once with
+            # the BLAS pool limited to one thread and once with all the threads it takes by default
+            def tiny_oracle():
+                t0 = time.perf_counter()
+                for layer, m in enumerate((1, 0, 1, 0)):
+                    draw = lambda kind, rows, heads, step=0: O.bf16_to_f64(synth.normal_bf16(
+                        0, synth.stream_id(kind, layer, step), (rows, heads, 64)))
+                    oc = O.KVCache(1, 2, 64)
+                    O.prefill(oc, [draw(synth.STREAM_Q, 512, 8)], [draw(synth.STREAM_K, 512, 2)],
+                              [draw(synth.STREAM_V, 512, 2)], [m], 16, 128)
+                    for step in range(16):
+                        O.decode_step(oc, draw(synth.STREAM_QDEC, 1, 8, step), draw(synth.STREAM_KDEC, 1, 2, step),
+                                      draw(synth.STREAM_VDEC, 1, 2, step), [m], 16, 128)
+                return time.perf_counter() - t0
+
+            tiny_oracle()                                        # first call pays imports and page faults
+            t_all = min(tiny_oracle() for _ in range(3))
+            try:
+                from threadpoolctl import threadpool_limits
+                with threadpool_limits(limits=1):
+                    t_one = min(tiny_oracle() for _ in range(3))
+            except Exception:
+                t_one = None
+            cpu_baseline["tiny_config_in_full"] = {
+                "what": "oracle wall-clock for the whole Tiny configuration (4 layers x [512-token prefill + 16 decode "
+                        "steps]), input generation included, best of 3",
+                "seconds_single_thread": t_one, "seconds_all_cores": t_all, "cores": cores,
+                "prefill_tokens_per_s_all_cores": 512 / t_all}
         del q, kn, vn, out, caches
         torch.cuda.empty_cache()
 
@@ -357,13 +411,16 @@ def main():
             "roofline": {"kernel": "decode_splitk_kernel<128, true> + decode_combine_kernel<128> (FA layers)",
                          "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": ach / PEAK_HBM_GBS,
-                         "traffic": measured_traffic("decode_fa_long_context_131072") if not args.small else None,
+                         "traffic": None, "traffic_note": "not the profiled workload",
                          "bytes_per_launch": bytes_fa,
                          "launch_ms": fa_avg},
             "sa_achieved_gbs": bytes_sa / (sa_avg * 1e-3) / 1e9 if sa_ms else None,
             "sparse_decode_residency": ring_info,
             "ms_per_step_mix_hip_graph": graph_ms,
         }
+        if not args.small:
+            decode["roofline"]["traffic"], decode["roofline"]["traffic_note"] = measured_traffic(
+                "decode_fa_long_context_131072", ["decode.hip", "flux_internal.h"])
         del kc, vc, dcaches
         torch.cuda.empty_cache()
 
@@ -471,11 +528,15 @@ def main():
 
     # ------------------------------------------------------------------ optional: the two other full-size workloads
     extra = None
-    if args.extra:
+    if args.small or args.no_extra or args.only != "all":
+        extra = {"not_run": "--small, --no-extra or --only given"}
+    else:
         extra = {}
+        long_form = args.extra
 
-        def timed(fn, reps):
-            fn()
+        def timed(fn, reps, warm=True):
+            if warm:
+                fn()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(reps):
@@ -504,8 +565,9 @@ def main():
                 F.flux_kv_append(ctx, caches4[l], HKV4, D, k4[0], v4[0], cu4, B4 * S4, S4)
                 F.flux_attn_prefill(ctx, cfg4, q4[0], cu4, S4, S4, caches4[l], m4[int(mask[l])], out4)
 
-        t4_mix = timed(lambda: step4(mask4), 3)
-        t4_fa = timed(lambda: step4(np.ones(L4, dtype=np.uint8)), 2)
+        reps4 = (3, 2) if long_form else (2, 1)
+        t4_mix = timed(lambda: step4(mask4), reps4[0])
+        t4_fa = timed(lambda: step4(np.ones(L4, dtype=np.uint8)), reps4[1])
         vis_sa4 = sum(min(i + 1, W4) + max(0, min(NS4, i + 1 - W4)) for i in range(S4))
         fl_fa4 = 4.0 * D * HQ4 * B4 * pairs_fa(S4)
         fl_sa4 = 4.0 * D * HQ4 * B4 * vis_sa4
@@ -516,8 +578,11 @@ def main():
             "ms_per_step_mix": t4_mix * 1e3, "ms_per_step_all_fa": t4_fa * 1e3,
             "tokens_per_s_mix": B4 * S4 / t4_mix, "tokens_per_s_all_fa": B4 * S4 / t4_fa,
             "all_fa_tflops": L4 * fl_fa4 / t4_fa / 1e12,
+            "mix_tflops": (n_fa4 * fl_fa4 + (L4 - n_fa4) * fl_sa4) / t4_mix / 1e12,
             "speedup_mix_vs_all_fa": t4_fa / t4_mix,
-            "predicted_speedup_from_flops": L4 * fl_fa4 / (n_fa4 * fl_fa4 + (L4 - n_fa4) * fl_sa4)}
+            "predicted_speedup_from_flops": L4 * fl_fa4 / (n_fa4 * fl_fa4 + (L4 - n_fa4) * fl_sa4),
+            "omega_msr": float((mask4 == 0).mean()),
+            "timed_steps_mix_and_all_fa": list(reps4), "warmup_steps": 1}
         del q4, k4, v4, out4, caches4
         torch.cuda.empty_cache()
 
@@ -540,18 +605,21 @@ def main():
         caches5 = [F.KVCache.empty(B5, HKV, cap5, D) for _ in range(L5)]
         cu5 = i32([0] + list(np.cumsum(lens5)))
         routed = torch.zeros(L5, B5, dtype=torch.uint8, device=dev)
+        logits5 = torch.zeros(L5, B5, 2, dtype=torch.float32, device=dev)
         ones5 = torch.ones(L5, B5, dtype=torch.uint8, device=dev)
 
         def prefill5(mask_dev, route):
             for l in range(L5):
                 if route:
-                    F.flux_router(ctx, q5, cu5, B5, hidden, pool, w1_5[0, l], None, w2_5[0, l], None, inner, mask_dev[l])
+                    F.flux_router(ctx, q5, cu5, B5, hidden, pool, w1_5[0, l], None, w2_5[0, l], None, inner, mask_dev[l],
+                                  logits5[l])
                 caches5[l].kv_len.zero_()
                 F.flux_kv_append(ctx, caches5[l], HKV, D, k5[0], v5[0], cu5, T5, smax5)
                 F.flux_attn_prefill(ctx, cfg, q5[0], cu5, smax5, smax5, caches5[l], mask_dev[l], out5)
 
-        t5_mix = timed(lambda: prefill5(routed, True), 2)
-        t5_fa = timed(lambda: prefill5(ones5, False), 1)
+        t5_mix = timed(lambda: prefill5(routed, True), 2 if long_form else 1)
+        t5_fa = timed(lambda: prefill5(ones5, False), 1, warm=long_form)
+        margin5 = float((logits5[..., 0] - logits5[..., 1]).abs().min())
         mask5 = routed.cpu().numpy()                       # read once after prefill: sizes the decode launches
         w_fa = {n: 4.0 * D * HQ * pairs_fa(n) for n in lens5}
         w_sa = {n: 4.0 * D * HQ * pairs_sa(n) for n in lens5}
@@ -587,7 +655,8 @@ def main():
             return (time.perf_counter() - t0) / steps
 
         td5_mix = decode_run(mask5, routed, n_steps5)
-        td5_fa = decode_run(np.ones_like(mask5), ones5, n_steps5 // 4)
+        n_steps5_fa = n_steps5 // 4
+        td5_fa = decode_run(np.ones_like(mask5), ones5, n_steps5_fa)
         rb = 2.0 * HKV * D * 2
         by_fa = L5 * sum(rb * n for n in lens5)
         by_mix = sum(rb * (lens5[b] if mask5[l, b] else min(lens5[b], NS + W)) for l in range(L5) for b in range(B5))
@@ -597,6 +666,11 @@ def main():
                         "prefill then %d decode steps" % (L5, lens5, T5, HQ, HKV, D, hidden, inner, pool, pool, NS, W, SEED5, n_steps5),
             "omega_msr": float((mask5 == 0).mean()),
             "sa_layers_per_sequence": [int((mask5[:, b] == 0).sum()) for b in range(B5)],
+            "router_min_logit_margin": margin5,
+            "router_min_logit_margin_note": "min |pi_FA - pi_SA| over the %d (sequence, layer) decisions, fp32 logits of "
+                                            "the device; decisions are bit-exact against the fp64 oracle above 1e-6" % (L5 * B5),
+            "prefill_timed_steps_routed_and_all_fa": [2 if long_form else 1, 1],
+            "decode_timed_steps_routed_and_all_fa": [n_steps5, n_steps5_fa],
             "prefill_ms_routed": t5_mix * 1e3, "prefill_ms_all_fa": t5_fa * 1e3,
             "prefill_tokens_per_s_routed": T5 / t5_mix, "prefill_tokens_per_s_all_fa": T5 / t5_fa,
             "prefill_speedup": t5_fa / t5_mix, "prefill_predicted_speedup_from_flops": work_fa / work_mix,

@@ -91,7 +91,8 @@ const char* flux_strerror(int code);
  * prefill, router and append need less than 64 KiB).  0 on invalid arguments. */
 size_t flux_workspace_needed(const flux_attn_cfg* cfg, int batch, int max_kv_len);
 
-/* Waits for `stream`, returns the sticky device status bits (>= 0) and clears them. */
+/* Returns the sticky device status bits (>= 0) and clears them.  Synchronous: copies the word back and
+ * waits for `stream`; when a bit was set it then writes the cleared word and waits for `stream` again. */
 int flux_last_device_status(flux_ctx* ctx, void* stream);
 
 /* Layer Router, hard-routing inference form (Sec. 3.1 "Architecture and Feature Extraction"

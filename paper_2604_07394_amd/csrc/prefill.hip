@@ -18,6 +18,8 @@
 // random bf16 data reaches 2030-2280 TFLOP/s with it and 1170-1450 with 32x32x16, whatever the number of
 // independent accumulators.
 // Only blocks that straddle the causal diagonal or a window / sink edge evaluate the element mask.
+#include <type_traits>
+
 #include "flux_internal.h"
 
 namespace flux {
@@ -52,6 +54,34 @@ __device__ __forceinline__ void dma16(const char* base /*uniform*/, int lane_off
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
 
+// All transfers of one wave for one whole tile in a single statement (four for K and four for V, or two and two):
+// the LDS destination of transfer t is the uniform base plus a compile-time offset, so M0 is produced by one
+// scalar add, and nothing is scheduled between the transfers.  A transfer keeps the issuing wave for about 64
+// cycles whatever surrounds it (measured: the vector memory port of a SIMD takes one lane's 16 bytes per cycle),
+// so their place in the iteration does not matter; they sit right behind the barrier, where the stage is free.
+#define FLUX_DMA_ONE(v, p, o) "s_add_u32 m0, %[lds], %[" o "]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[" v "], %[" p "]\n\t"
+template <int OFF, int KT>   // OFF: LDS offset of the stage; KT: bytes from the K tile to the V tile of a stage
+__device__ __forceinline__ void dma_tile4(const char* kt, const char* vt, const int (&ko)[4], const int (&vo)[4],
+                                          uint32_t lds_base) {
+  asm volatile(FLUX_DMA_ONE("k0", "kt", "o0") FLUX_DMA_ONE("k1", "kt", "o1") FLUX_DMA_ONE("k2", "kt", "o2")
+               FLUX_DMA_ONE("k3", "kt", "o3") FLUX_DMA_ONE("v0", "vt", "o4") FLUX_DMA_ONE("v1", "vt", "o5")
+               FLUX_DMA_ONE("v2", "vt", "o6") FLUX_DMA_ONE("v3", "vt", "o7")
+               : : [k0] "v"(ko[0]), [k1] "v"(ko[1]), [k2] "v"(ko[2]), [k3] "v"(ko[3]), [v0] "v"(vo[0]), [v1] "v"(vo[1]),
+                   [v2] "v"(vo[2]), [v3] "v"(vo[3]), [kt] "s"(kt), [vt] "s"(vt), [lds] "s"(lds_base), [o0] "i"(OFF),
+                   [o1] "i"(OFF + 4096), [o2] "i"(OFF + 8192), [o3] "i"(OFF + 12288), [o4] "i"(OFF + KT),
+                   [o5] "i"(OFF + KT + 4096), [o6] "i"(OFF + KT + 8192), [o7] "i"(OFF + KT + 12288)
+               : "memory", "m0", "scc");
+}
+template <int OFF, int KT>
+__device__ __forceinline__ void dma_tile2(const char* kt, const char* vt, const int (&ko)[2], const int (&vo)[2],
+                                          uint32_t lds_base) {
+  asm volatile(FLUX_DMA_ONE("k0", "kt", "o0") FLUX_DMA_ONE("k1", "kt", "o1") FLUX_DMA_ONE("v0", "vt", "o4")
+               FLUX_DMA_ONE("v1", "vt", "o5")
+               : : [k0] "v"(ko[0]), [k1] "v"(ko[1]), [v0] "v"(vo[0]), [v1] "v"(vo[1]), [kt] "s"(kt), [vt] "s"(vt),
+                   [lds] "s"(lds_base), [o0] "i"(OFF), [o1] "i"(OFF + 4096), [o4] "i"(OFF + KT), [o5] "i"(OFF + KT + 4096)
+               : "memory", "m0", "scc");
+}
+
 template <int D>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int BN = 64;                  // keys per iteration: two halves of 32, the K dimension of one PV MFMA
@@ -78,6 +108,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int VPW = (NVI + 3) / 4;         // V transfers per wave
   constexpr int RPI = 64 / CPR;              // V rows per transfer
   static_assert(BN * CPR % 64 == 0, "V tile must split into whole wave transfers");
+  static_assert(NKI % 4 == 0 && NVI % 4 == 0 && (KPW == 4 || KPW == 2) && VPW == KPW, "every wave issues the same transfers");
 
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
 
@@ -204,32 +235,28 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   for (int t = 0; t < VPW; ++t) v_off[t] = v_slot(t, BN);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(FLUX_LDS char*)smem;
 
-  auto issue_tile = [&](int it, int stage) {
-    const int j0 = (it < n_a ? it : win0 + (it - n_a)) * BN;
+  const uint32_t lds_w = lds0 + 1024 * w;                    // this wave's 1 KB slot inside every 4 KB of a stage
+
+  // tile index (in units of BN keys) of iteration `it`: the blocks [0, n_a) first, then [win0, win0 + n_b)
+  auto tile_of = [&](int it) { return it < n_a ? it : win0 + (it - n_a); };
+
+  // All transfers of one tile with rows clamped to the cached length: the first tile, and a last tile that
+  // is only partly inside the cache.
+  auto issue_tile_clamped = [&](int it, int stage) {
+    const int j0 = tile_of(it) * BN;
     const int rmax = len - 1 - j0;                           // rows past the cached length are clamped
     const char* kt = kbase + (int64_t)j0 * pitch_g;
     const char* vt = vbase + (int64_t)j0 * pitch_g;
-    const uint32_t lk = lds0 + stage * STAGE + 1024 * w;
-    const uint32_t lv = lk + KTILE;
-    const bool whole = rmax >= BN - 1;                       // uniform: only the last tile can be partial
-    if (whole) {
+    const uint32_t lk = lds_w + stage * STAGE;
 #pragma unroll
-      for (int t = 0; t < KPW; ++t)
-        if (4 * t + 3 < NKI || w + 4 * t < NKI) dma16(kt, k_off[t], lk + 4096 * t);
+    for (int t = 0; t < KPW; ++t)
+      if (4 * t + 3 < NKI || w + 4 * t < NKI) dma16(kt, k_slot(t, rmax), lk + 4096 * t);
 #pragma unroll
-      for (int t = 0; t < VPW; ++t)
-        if (4 * t + 3 < NVI || w + 4 * t < NVI) dma16(vt, v_off[t], lv + 4096 * t);
-    } else {
-#pragma unroll
-      for (int t = 0; t < KPW; ++t)
-        if (4 * t + 3 < NKI || w + 4 * t < NKI) dma16(kt, k_slot(t, rmax), lk + 4096 * t);
-#pragma unroll
-      for (int t = 0; t < VPW; ++t)
-        if (4 * t + 3 < NVI || w + 4 * t < NVI) dma16(vt, v_slot(t, rmax), lv + 4096 * t);
-    }
+    for (int t = 0; t < VPW; ++t)
+      if (4 * t + 3 < NVI || w + 4 * t < NVI) dma16(vt, v_slot(t, rmax), lk + KTILE + 4096 * t);
   };
 
-  // ---- per-lane LDS read offsets (bytes, relative to the stage)
+  // ---- per-lane LDS read offsets (bytes, relative to stage 0; the stage is added as an immediate)
   // K fragment (kb, kc): row 16*kb + n, logical chunk 4*kc + g (d = 32*kc + 8*g ..), swizzled by the row
   const int k_xr = D == 128 ? n : (n >> 1);
   int k_rd[KC];
@@ -244,6 +271,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   for (int db = 0; db < DB; ++db) v_rd[db] = KTILE + v_row * ROWB + ((db ^ v_xr) * 32) + (n & 3) * 8;
 
   float m_ref[2] = {-INFINITY, -INFINITY};                   // the score the exponents of a row refer to
+  float mneg[2] = {0.f, 0.f};                                // -m_ref * scale_log2 (0 while a row has no reference yet)
   float l_run[2] = {0.f, 0.f};                               // this lane's part of the row sums
   bool all_ref = false;                                      // wave-uniform: every row of the wave has a reference
   f32x4 o[DB][2];
@@ -252,28 +280,52 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) o[i][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (n_iter > 0) issue_tile(0, 0);
-  for (int it = 0; it < n_iter; ++it) {
-    const int stage = it & 1;
+  // ---- which iterations are PLAIN for this wave: the wave is active, every key of the block is visible to
+  // every row of the wave (no element mask, nothing to skip).  In tile indices: the block ends at or before the
+  // wave's first row (tile < c_end), and for SA it lies wholly inside the sinks (tile < s_full) or starts at
+  // or after the window start of the wave's LAST row (tile >= w_first_full).  As iteration ranges:
+  // [0, pa_end) and [pb_begin, pb_end).  A wave issues its instructions in order and two waves share a SIMD, so
+  // every instruction of the loop shows in its time: the plain iterations (all but a few per workgroup) skip the
+  // mask flags and the block's first key altogether.
+  int pa_end = 0, pb_begin = 0, pb_end = 0;
+  if (wave_active) {
+    const int c_end = (i_w_min + 1) / BN;
+    if (!sa) {
+      pa_end = min(n_a, c_end);
+    } else {
+      pa_end = min(min(n_a, c_end), a.sink_lim / BN);
+      const int w_first_full = (w_lo_last + BN - 1) / BN;
+      pb_begin = n_a + max(w_first_full - win0, 0);
+      pb_end = min(n_a + max(c_end - win0, 0), n_iter);
+    }
+  }
+  // the last tile may be only partly inside the cache; every other tile is whole
+  const bool last_whole = n_iter > 0 && len - 1 - tile_of(n_iter - 1) * BN >= BN - 1;
+  const int lim_whole = last_whole ? n_iter : n_iter - 1;    // iterations it + 1 < lim_whole transfer a whole tile
+  const unsigned pb_len = pb_end > pb_begin ? pb_end - pb_begin : 0;
+  const int64_t step_b = (int64_t)BN * pitch_g;              // bytes from one key block to the next
+  const int64_t jump_b = (int64_t)(win0 - n_a + 1) * step_b; // from the last sink block to the first window block
+  const char* kt_n = kbase + (int64_t)(n_iter > 1 ? tile_of(1) : 0) * step_b;   // the tile the next transfer brings in
+  const char* vt_n = vbase + (int64_t)(n_iter > 1 ? tile_of(1) : 0) * step_b;
+
+  // One iteration.  STG (the LDS stage of this tile) is a compile-time constant: the loop is unrolled by two so
+  // that every LDS address is a loop-invariant register plus an immediate.
+  auto iteration = [&](int it, auto stg_c) {
+    constexpr int STG = decltype(stg_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this wave's transfers have landed
     __syncthreads();                                         // ... and everyone's; the other stage is free
-    if (it + 1 < n_iter) issue_tile(it + 1, stage ^ 1);      // in flight during the math below
-
-    const int j0 = (it < n_a ? it : win0 + (it - n_a)) * BN;
-    // does this wave see anything in the block, and does it need the element mask?
-    bool skip = !wave_active || j0 > i_w_max;
-    const bool mask_causal = j0 + BN - 1 > i_w_min;          // the diagonal crosses the block
-    bool mask_edge = false;                                  // a window or sink edge falls inside the block
-    if (sa) {
-      const bool all_sink = j0 + BN <= a.sink_lim;
-      if (!all_sink) {
-        if (j0 >= a.sink_lim && j0 + BN - 1 < w_lo_first) skip = true;            // before every window
-        mask_edge = j0 < w_lo_last;
-      }
+    if (it + 1 < lim_whole) {                                // the next tile, in flight during the math below
+      if constexpr (KPW == 4) dma_tile4<(STG ^ 1) * STAGE, KTILE>(kt_n, vt_n, k_off, v_off, lds_w);
+      else dma_tile2<(STG ^ 1) * STAGE, KTILE>(kt_n, vt_n, k_off, v_off, lds_w);
+      const int64_t adv = it + 2 == n_a ? jump_b : step_b;   // on to the tile after it (the window part starts at win0)
+      kt_n += adv;
+      vt_n += adv;
+    } else if (it + 1 < n_iter) {
+      issue_tile_clamped(it + 1, STG ^ 1);                   // a last tile that is only partly inside the cache
     }
-    if (skip) continue;
+    const bool plain = it < pa_end || (unsigned)(it - pb_begin) < pb_len;
 
-    FLUX_LDS char* st = (FLUX_LDS char*)smem + stage * STAGE;
+    FLUX_LDS char* st = (FLUX_LDS char*)smem + STG * STAGE;
     // Order of the block, written out so that every LDS read is issued well before its use (the fences keep
     // the compiler from sinking the reads back to their uses):
     //   K fragments of both halves | S^T half 0 | V fragments of half 0 | S^T half 1 | weights |
@@ -317,7 +369,6 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        const float mneg = m_ref[qb] == -INFINITY ? 0.f : -m_ref[qb] * a.scale_log2;
         l_blk[qb] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -325,8 +376,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const f32x4& sv = s[2 * ks + (t >> 1)][qb];
-            const float p0 = fast_exp2(__builtin_fmaf(sv[2 * (t & 1)], a.scale_log2, mneg));
-            const float p1 = fast_exp2(__builtin_fmaf(sv[2 * (t & 1) + 1], a.scale_log2, mneg));
+            const float p0 = fast_exp2(__builtin_fmaf(sv[2 * (t & 1)], a.scale_log2, mneg[qb]));
+            const float p1 = fast_exp2(__builtin_fmaf(sv[2 * (t & 1) + 1], a.scale_log2, mneg[qb]));
             pk[t] = pack_bf16(p0, p1);
             // the denominator sums the same rounded weights the numerator uses
             l_blk[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[t]), ones, l_blk[qb], false);
@@ -342,7 +393,55 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
         for (int qb = 0; qb < 2; ++qb)
           o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[ks][db], pf[qb][ks], o[db][qb], 0, 0, 0);
     };
+    // Only when a row has no reference yet, or some weight of the block left the guarded range (or
+    // overflowed), does the wave take the block's maximum, move the reference there (rescaling l and O) and
+    // redo the weights.  In the steady state the maximum, its cross-lane steps and the rescale are not executed.
+    auto weights_guarded = [&]() {
+      weights();
+      if (!all_ref || __builtin_amdgcn_ballot_w64(!(l_blk[0] < kWeightGuard) | !(l_blk[1] < kWeightGuard)) != 0) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          float mloc = s[0][qb][0];
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mloc = fmaxf(mloc, s[kb][qb][i]);
+          mloc = fmaxf(mloc, __shfl_xor(mloc, 16));                              // over the 4 lanes of the row
+          mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+          const float m_new = fmaxf(m_ref[qb], mloc);
+          if (m_new > m_ref[qb]) {                                               // false while both are -inf
+            const float al = fast_exp2((m_ref[qb] - m_new) * a.scale_log2);      // 0 for a row's first reference
+            l_run[qb] *= al;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) o[db][qb] *= al;
+            m_ref[qb] = m_new;
+            mneg[qb] = -m_new * a.scale_log2;
+          }
+        }
+        weights();
+        all_ref = __builtin_amdgcn_ballot_w64((m_ref[0] == -INFINITY) | (m_ref[1] == -INFINITY)) == 0;
+      }
+      l_run[0] += l_blk[0];
+      l_run[1] += l_blk[1];
+    };
 
+    // a block that an edge of the visible set crosses, or that this wave does not see at all, needs the
+    // block's first key and the mask flags; a plain block needs none of that scalar work
+    int j0 = 0;
+    bool mask_causal = false, mask_edge = false;
+    if (!plain) {
+      j0 = tile_of(it) * BN;
+      bool skip = !wave_active || j0 > i_w_max;
+      mask_causal = j0 + BN - 1 > i_w_min;                   // the diagonal crosses the block
+      if (sa) {
+        const bool all_sink = j0 + BN <= a.sink_lim;
+        if (!all_sink) {
+          if (j0 >= a.sink_lim && j0 + BN - 1 < w_lo_first) skip = true;          // before every window
+          mask_edge = j0 < w_lo_last;                        // a window or sink edge falls inside the block
+        }
+      }
+      if (skip) return;
+    }
     load_k(0);
     load_k(1);
     __builtin_amdgcn_sched_barrier(0);
@@ -352,8 +451,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     __builtin_amdgcn_sched_barrier(0);
     scores(1);
     __builtin_amdgcn_sched_barrier(0);
-    // Element masks, only on blocks an edge of the visible set crosses.  Key j = j0 + 4*g + c with the constant
-    // c = 16*kb + i, so each bound is moved into the lane once (bound - j0 - 4*g) and compared with constants.
+    // Element masks.  Key j = j0 + 4*g + c with the constant c = 16*kb + i, so each bound is moved into the
+    // lane once (bound - j0 - 4*g) and compared with constants.
     if (mask_edge) {
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
@@ -377,40 +476,19 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           for (int i = 0; i < 4; ++i) s[kb][qb][i] = 16 * kb + i <= hi ? s[kb][qb][i] : -INFINITY;
       }
     }
-    weights();
-    // Only when a row has no reference yet, or some weight of the block left the guarded range (or
-    // overflowed), does the wave take the block's maximum, move the reference there (rescaling l and O) and
-    // redo the weights.  In the steady state the maximum, its cross-lane steps and the rescale are not executed.
-    if (!all_ref || __builtin_amdgcn_ballot_w64(!(l_blk[0] < kWeightGuard) | !(l_blk[1] < kWeightGuard)) != 0) {
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        float mloc = s[0][qb][0];
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) mloc = fmaxf(mloc, s[kb][qb][i]);
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));                              // over the 4 lanes of the row
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float m_new = fmaxf(m_ref[qb], mloc);
-        if (m_new > m_ref[qb]) {                                               // false while both are -inf
-          const float al = fast_exp2((m_ref[qb] - m_new) * a.scale_log2);      // 0 for a row's first reference
-          l_run[qb] *= al;
-#pragma unroll
-          for (int db = 0; db < DB; ++db) o[db][qb] *= al;
-          m_ref[qb] = m_new;
-        }
-      }
-      weights();
-      all_ref = __builtin_amdgcn_ballot_w64((m_ref[0] == -INFINITY) | (m_ref[1] == -INFINITY)) == 0;
-    }
-    l_run[0] += l_blk[0];
-    l_run[1] += l_blk[1];
+    weights_guarded();
     __builtin_amdgcn_sched_barrier(0);
     load_v(1);
     __builtin_amdgcn_sched_barrier(0);
     accumulate(0);
     __builtin_amdgcn_sched_barrier(0);
     accumulate(1);
+  };
+
+  if (n_iter > 0) issue_tile_clamped(0, 0);
+  for (int it = 0; it < n_iter; it += 2) {
+    iteration(it, std::integral_constant<int, 0>());
+    if (it + 1 < n_iter) iteration(it + 1, std::integral_constant<int, 1>());
   }
 
   // ---- normalise and store: lane (n, g) holds d = 16*db + 4*g .. +3 of its two query rows

@@ -25,6 +25,14 @@ What it follows (paper sections / equations):
   kernel needs (the sinks and the last ``window`` positions); ``RingKVCache``
   stores exactly those and ``decode_step_ring`` attends over what is stored.
 * Model Sparsity Ratio, Eq. (3) of Sec. 2.3, at layer granularity.
+* Block-sparse attention, Eq. (2) with an arbitrary set of key BLOCKS per query block (the substrate the
+  other sparse modes of Sec. 4.1 need): ``attention(..., block_mask=...)``.  A block of 64 positions is
+  "the minimum unit of sparsity" (App. C.3).
+* XAttention block selection (the XA mode of Sec. 4.1; Table 3: stride 16, threshold 0.9, selection mode
+  "Inverse", block 64): ``xa_block_mass`` and ``xa_select``.  The paper names the method ("Block Sparse
+  Attention with Antidiagonal Scoring") and its parameters and nothing else, so what is computed here is
+  THIS BUILD'S READING of those words, written out in the two functions' docstrings; its agreement with
+  the paper's own XA kernels is parity-unpinned (the functions themselves are pinned, see below).
 
 Conventions: ``mode`` 1 = FA, 0 = SA (the paper's ``r_hard``).  All arrays are
 float64; bf16 inputs are widened exactly by ``bf16_to_f64`` first.  Positions
@@ -37,8 +45,14 @@ invariance, brute-force enumeration on 8-token cases, a textbook dense
 formula, GQA by head repetition, decode == last prefill row, a hand-computed
 router, argmax flip and tie; for the ring residency: stored positions against
 their closed form, equality with the full-cache SA decode step by step across
-several wrap-arounds, and compaction of a prompt against row-by-row appends.
-No function here is parity-unpinned.
+several wrap-arounds, and compaction of a prompt against row-by-row appends;
+for the block mask: brute force, the all-true lower triangle equals FA bit for
+bit, the sink + window block pattern equals the block-granular SA bit for bit;
+for the XA selection: brute-force element sampling against the strided form,
+masses that sum to one, closed forms for constant inputs, threshold limits and
+monotonicity.  Every function is pinned against the mathematics it states; what
+is parity-unpinned is whether ``xa_block_mass`` / ``xa_select`` are the paper's
+XA (it defines neither).
 """
 from __future__ import annotations
 
@@ -88,6 +102,29 @@ def mask_matrix(n_q: int, n_kv: int, mode: int, n_sink: int, window: int, block:
     return visible(i, j, mode, n_sink, window, block)
 
 
+BLOCK = 64          # positions per block of a block mask (App. C.3: "the minimum unit of sparsity")
+
+
+def block_mask_matrix(n_q: int, n_kv: int, block_mask: np.ndarray, block: int = BLOCK) -> np.ndarray:
+    """Explicit boolean mask [n_q, n_kv] of a block-sparse pattern.
+
+    Positions are grouped into blocks of ``block``; query position ``i`` (row
+    ``r`` is position ``n_kv - n_q + r``) sees key ``j`` iff ``j <= i`` and the
+    pair (block of i, block of j) is kept.  ``block_mask[rq, bj]`` is the keep
+    flag of key block ``bj`` for the query block ``(n_kv - n_q) // block + rq``
+    (row 0 is the block of the call's first query).  The block that holds the
+    query's own position is always kept, whatever the flag says: every query
+    must see at least itself.
+    """
+    pos0 = n_kv - n_q
+    i = (pos0 + np.arange(n_q))[:, None]
+    j = np.arange(n_kv)[None, :]
+    bi, bj = i // block, j // block
+    bm = np.asarray(block_mask, dtype=bool)
+    keep = bm[bi - pos0 // block, bj] | (bi == bj)
+    return (j <= i) & keep
+
+
 # --------------------------------------------------------------------------- attention
 
 def softmax_rows(s: np.ndarray, mask: np.ndarray) -> np.ndarray:
@@ -99,11 +136,16 @@ def softmax_rows(s: np.ndarray, mask: np.ndarray) -> np.ndarray:
 
 
 def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mode: int, n_sink: int, window: int,
-              scale: float | None = None, return_probs: bool = False, block: int = 1):
+              scale: float | None = None, return_probs: bool = False, block: int = 1, block_mask=None,
+              mask_block: int = BLOCK):
     """One sequence, one layer, explicit mask matrix.
 
     q [n_q, Hq, D], k and v [n_kv, Hkv, D] (fp64).  Returns out [n_q, Hq, D]
-    (and P [Hq, n_q, n_kv] if asked).
+    (and P [Hq, n_q, n_kv] if asked).  With ``block_mask`` (one keep matrix
+    [query blocks, key blocks] for all heads, or [Hq, query blocks, key blocks])
+    the visible set is the block-sparse one of ``block_mask_matrix`` with blocks
+    of ``mask_block`` positions, and ``mode``, ``n_sink``, ``window``, ``block``
+    are not used.
     """
     n_q, hq, d = q.shape
     n_kv, hkv, _ = k.shape
@@ -111,13 +153,16 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mode: int, n_sink: in
     g = hq // hkv
     if scale is None:
         scale = 1.0 / np.sqrt(d)
-    mask = mask_matrix(n_q, n_kv, mode, n_sink, window, block)
+    mask = mask_matrix(n_q, n_kv, mode, n_sink, window, block) if block_mask is None else None
     out = np.empty((n_q, hq, d), dtype=np.float64)
     probs = np.empty((hq, n_q, n_kv), dtype=np.float64) if return_probs else None
     for h in range(hq):
         kh = k[:, h // g, :]
         vh = v[:, h // g, :]
         s = scale * (q[:, h, :] @ kh.T)
+        if block_mask is not None:
+            bm = np.asarray(block_mask)
+            mask = block_mask_matrix(n_q, n_kv, bm[h] if bm.ndim == 3 else bm, mask_block)
         p = softmax_rows(s, mask)
         out[:, h, :] = p @ vh
         if return_probs:
@@ -253,6 +298,88 @@ def compact_to_ring(full: KVCache, ring: RingKVCache) -> None:
     a sparse layer needs: the same state as appending the prompt to an empty ring row by row."""
     for b in range(len(full.k)):
         ring.append(b, full.k[b], full.v[b])
+
+
+# --------------------------------------------------------------------------- XAttention block selection
+
+def xa_block_mass(q: np.ndarray, k: np.ndarray, stride: int = 16, block: int = BLOCK, scale: float | None = None):
+    """Approximate attention mass of every (query block, key block) pair of ONE head from antidiagonal samples.
+
+    The reading taken of "Block Sparse Attention with Antidiagonal Scoring", stride 16, selection mode
+    "Inverse", block 64 (Sec. 4.1, Table 3), for a whole prompt (``n`` queries at positions 0..n-1 over the
+    same ``n`` keys; q, k [n, D]):
+
+    1. The scaled score matrix ``scale * q k^T`` is cut into squares of ``stride x stride`` positions.  Of
+       square (a, b) (query positions ``stride*a ..``, key positions ``stride*b ..``) only the ANTIDIAGONAL
+       is looked at: row offset r against column offset ``stride - 1 - r`` (the query rows taken in inverse
+       order against the key columns: the "Inverse" mode), and of those samples only the causal ones
+       (key position <= query position).  ``e[a, b]`` is the MEAN of the square's causal samples (the
+       "normalisation" App. C.3 mentions: the sampled sum over the number of samples); squares without a
+       causal sample (b > a) do not exist.
+    2. Each row ``a`` of ``e`` is turned into probabilities over its existing squares b <= a by a softmax:
+       the approximate attention of those ``stride`` queries at a granularity of ``stride`` keys.
+    3. The mass of the block pair (I, J) is the sum of those probabilities over the squares inside it
+       (``block / stride`` rows by ``block / stride`` columns), divided by the number of rows of ``e`` the
+       query block has, so that the masses of one query block sum to one.
+
+    Returns ``mass`` [n_qblocks, n_kblocks] (fp64; zero above the block diagonal).  ``n`` need not be a
+    multiple of ``block`` or ``stride``: trailing positions form shorter squares and blocks.
+    """
+    n, d = q.shape
+    assert k.shape == (n, d) and block % stride == 0
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    n_sq = -(-n // stride)
+    e = np.full((n_sq, n_sq), -np.inf)
+    s = scale * (q @ k.T)
+    for a in range(n_sq):
+        for b in range(a + 1):
+            tot, cnt = 0.0, 0
+            for r in range(stride):
+                i, j = stride * a + r, stride * b + stride - 1 - r
+                if i < n and j < n and j <= i:
+                    tot += s[i, j]
+                    cnt += 1
+            if cnt:
+                e[a, b] = tot / cnt
+    p = np.zeros_like(e)
+    for a in range(n_sq):
+        row = e[a, : a + 1]
+        ok = np.isfinite(row)
+        w = np.exp(row[ok] - row[ok].max())
+        p[a, : a + 1][ok] = w / w.sum()
+    per = block // stride
+    n_blk = -(-n // block)
+    mass = np.zeros((n_blk, n_blk))
+    for bi in range(n_blk):
+        rows = p[per * bi: per * (bi + 1)]
+        for bj in range(bi + 1):
+            mass[bi, bj] = rows[:, per * bj: per * (bj + 1)].sum() / rows.shape[0]
+    return mass
+
+
+def xa_select(q: np.ndarray, k: np.ndarray, stride: int = 16, threshold: float = 0.9, block: int = BLOCK,
+              scale: float | None = None, return_mass: bool = False):
+    """Key blocks every query block of ONE head keeps (Table 3: threshold 0.9).
+
+    For query block I the key blocks are taken in descending order of ``xa_block_mass`` until the masses
+    taken reach ``threshold``; every block whose mass equals that of the last one taken is kept as well (so
+    the result does not depend on how equal masses are ordered).  The diagonal block (the queries' own
+    positions) is always kept.  Returns a boolean matrix [n_qblocks, n_kblocks] to be used as the
+    ``block_mask`` of ``attention``.
+    """
+    mass = xa_block_mass(q, k, stride, block, scale)
+    n_blk = mass.shape[0]
+    keep = np.zeros((n_blk, n_blk), dtype=bool)
+    for bi in range(n_blk):
+        m = mass[bi, : bi + 1]
+        order = np.argsort(-m, kind="stable")
+        csum = np.cumsum(m[order])
+        cut = int(np.searchsorted(csum, threshold * csum[-1], side="left"))    # first prefix reaching the threshold
+        cut = min(cut, bi)
+        keep[bi, : bi + 1] = m >= m[order[cut]]
+        keep[bi, bi] = True
+    return (keep, mass) if return_mass else keep
 
 
 # --------------------------------------------------------------------------- router

@@ -421,3 +421,161 @@ def test_block_granular_decode_equals_last_prefill_row():
     cache.append(0, k[:-1], v[:-1])
     step = O.decode_step(cache, q[-1][None], k[-1][None], v[-1][None], [SA], n_sink, window, block=block)
     assert np.allclose(step[0], whole[-1], rtol=0, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- block-sparse mask (Eq. 2 over key blocks)
+
+def brute_force_block_sparse(q, k, v, bm, blk):
+    """Pure-Python enumeration: pair (i, j) counts iff j <= i and (its block pair is kept or is the diagonal)."""
+    n_q, hq, d = q.shape
+    n_kv, hkv, _ = k.shape
+    g = hq // hkv
+    pos0 = n_kv - n_q
+    out = np.zeros((n_q, hq, d))
+    for r in range(n_q):
+        i = pos0 + r
+        for h in range(hq):
+            num = [0.0] * d
+            den = 0.0
+            for j in range(n_kv):
+                if j > i:
+                    continue
+                if not (bm[i // blk - pos0 // blk][j // blk] or i // blk == j // blk):
+                    continue
+                sc = sum(q[r, h, t] * k[j, h // g, t] for t in range(d)) / math.sqrt(d)
+                w = math.exp(sc)
+                den += w
+                for t in range(d):
+                    num[t] += w * v[j, h // g, t]
+            out[r, h] = [x / den for x in num]
+    return out
+
+
+@pytest.mark.parametrize("n_q,n_kv", [(19, 19), (7, 19), (1, 19), (12, 20)])
+def test_block_sparse_attention_matches_brute_force(n_q, n_kv):
+    blk = 4
+    q, k, v = make_qkv(61, n_q, n_kv, 4, 2, 3)
+    n_kb = -(-n_kv // blk)
+    n_qb = (n_kv - 1) // blk - (n_kv - n_q) // blk + 1
+    bm = rng(62).random((n_qb, n_kb)) < 0.4
+    got = O.attention(q, k, v, FA, 0, 1, block_mask=bm, mask_block=blk)
+    assert np.abs(got - brute_force_block_sparse(q, k, v, bm, blk)).max() < 1e-12
+    # per-head masks: head h uses its own matrix
+    bmh = rng(63).random((4, n_qb, n_kb)) < 0.5
+    got_h = O.attention(q, k, v, FA, 0, 1, block_mask=bmh, mask_block=blk)
+    for h in range(4):
+        one = O.attention(q, k, v, FA, 0, 1, block_mask=bmh[h], mask_block=blk)
+        assert np.array_equal(got_h[:, h], one[:, h])
+
+
+def test_block_mask_all_true_is_fa_and_sink_window_blocks_are_block_granular_sa():
+    blk, n = 8, 100
+    q, k, v = make_qkv(64, n, n, 4, 2, 8)
+    nb = -(-n // blk)
+    assert np.array_equal(O.attention(q, k, v, FA, 0, 1, block_mask=np.ones((nb, nb), bool), mask_block=blk),
+                          O.attention(q, k, v, FA, 0, 1))
+    # the streaming pattern written as a block mask: first ceil(n_sink/blk) blocks + the ceil(window/blk) newest
+    n_sink, window = 10, 20
+    bi, bj = np.arange(nb)[:, None], np.arange(nb)[None, :]
+    bm = (bj < -(-n_sink // blk)) | (bi - bj < -(-window // blk))
+    assert np.array_equal(O.attention(q, k, v, FA, 0, 1, block_mask=bm, mask_block=blk),
+                          O.attention(q, k, v, SA, n_sink, window, block=blk))
+    # an all-false mask still keeps every query's own block (nothing else)
+    diag_only = O.attention(q, k, v, FA, 0, 1, block_mask=np.zeros((nb, nb), bool), mask_block=blk)
+    assert np.array_equal(diag_only, O.attention(q, k, v, FA, 0, 1, block_mask=np.eye(nb, dtype=bool), mask_block=blk))
+    assert np.array_equal(diag_only[:blk], O.attention(q, k, v, FA, 0, 1)[:blk])    # block row 0 is plain causal
+
+
+# ----------------------------------------------------------------------------- XAttention block selection (this build's reading)
+
+def xa_mass_independent(q, k, stride, blk):
+    """The same masses from a different formulation: the sampled pairs are those with
+    (i + j) % stride == stride - 1 (the antidiagonals of the stride x stride squares), found by scanning the
+    whole causal score matrix."""
+    n, d = q.shape
+    n_sq = -(-n // stride)
+    tot = np.zeros((n_sq, n_sq))
+    cnt = np.zeros((n_sq, n_sq))
+    for i in range(n):
+        for j in range(i + 1):
+            if (i + j) % stride == stride - 1:
+                tot[i // stride, j // stride] += float(q[i] @ k[j]) / math.sqrt(d)
+                cnt[i // stride, j // stride] += 1
+    per = blk // stride
+    n_blk = -(-n // blk)
+    mass = np.zeros((n_blk, n_blk))
+    for a in range(n_sq):
+        cols = [b for b in range(a + 1) if cnt[a, b] > 0]
+        e = np.array([tot[a, b] / cnt[a, b] for b in cols])
+        w = np.exp(e - e.max())
+        w /= w.sum()
+        rows_in_block = min(per, n_sq - (a // per) * per)
+        for b, x in zip(cols, w):
+            mass[a // per, b // per] += x / rows_in_block
+    return mass
+
+
+@pytest.mark.parametrize("n,stride,blk", [(64, 4, 8), (61, 4, 8), (50, 2, 4), (96, 16, 32)])
+def test_xa_block_mass_against_independent_scan(n, stride, blk):
+    r = rng(71)
+    q, k = r.standard_normal((n, 6)), r.standard_normal((n, 6))
+    mass = O.xa_block_mass(q, k, stride, blk)
+    assert np.abs(mass - xa_mass_independent(q, k, stride, blk)).max() < 1e-12
+    assert np.abs(mass.sum(axis=1) - 1.0).max() < 1e-12                 # a query block's masses sum to one
+    assert (np.triu(mass, 1) == 0).all()                                # nothing above the block diagonal
+    # strided form (what a fast kernel computes): square (a, b) is one dot product of the stride query rows
+    # in order against the stride key rows in inverse order, over stride * D numbers
+    if n % stride == 0:
+        qr = q.reshape(n // stride, stride * 6)
+        kr = k.reshape(n // stride, stride, 6)[:, ::-1].reshape(n // stride, stride * 6)
+        e = (qr @ kr.T) / math.sqrt(6) / stride
+        a, b = 3, 1                                                      # an off-diagonal square: all samples causal
+        s = (q @ k.T) / math.sqrt(6)
+        assert abs(e[a, b] - np.mean([s[stride * a + t, stride * b + stride - 1 - t] for t in range(stride)])) < 1e-12
+
+
+def test_xa_constant_inputs_closed_form():
+    """Equal scores everywhere: row a of the squares spreads its probability evenly over its a + 1 squares."""
+    n, stride, blk = 64, 4, 16
+    q = np.ones((n, 3))
+    k = np.ones((n, 3))
+    mass = O.xa_block_mass(q, k, stride, blk)
+    per = blk // stride
+    for bi in range(n // blk):
+        for bj in range(bi + 1):
+            expect = sum(len([b for b in range(per * bj, per * (bj + 1)) if b <= a]) / (a + 1)
+                         for a in range(per * bi, per * (bi + 1))) / per
+            assert abs(mass[bi, bj] - expect) < 1e-12
+
+
+def test_xa_select_threshold_limits_monotonicity_and_a_dominant_key():
+    n, stride, blk = 128, 4, 16
+    r = rng(72)
+    q, k = r.standard_normal((n, 8)), r.standard_normal((n, 8))
+    nb = n // blk
+    tri = np.tril(np.ones((nb, nb), bool))
+    assert np.array_equal(O.xa_select(q, k, stride, 1.0, blk), tri)     # everything with mass is needed to reach 1
+    keep0, mass = O.xa_select(q, k, stride, 1e-9, blk, return_mass=True)
+    for bi in range(nb):                                                # only the heaviest block, and the diagonal
+        assert set(np.nonzero(keep0[bi])[0]) == {int(np.argmax(mass[bi, :bi + 1])), bi}
+    prev = keep0
+    for t in (0.3, 0.6, 0.9, 0.99):
+        cur, m = O.xa_select(q, k, stride, t, blk, return_mass=True)
+        assert (cur | ~prev).all()                                      # a larger threshold never drops a block
+        for bi in range(nb):
+            kept = m[bi][cur[bi]].sum()
+            assert kept >= t - 1e-12                                    # the kept blocks reach the threshold ...
+            off_diag = cur[bi].copy()
+            off_diag[bi] = False
+            if off_diag.any():                                          # ... and the blocks strictly heavier than the
+                lightest = m[bi][off_diag].min()                        # lightest kept one would not have reached it
+                assert m[bi, :bi + 1][m[bi, :bi + 1] > lightest].sum() < t
+        prev = cur
+    # one key every query points at: its block takes the mass, and the selection is that block plus the diagonal
+    k2 = 0.01 * r.standard_normal((n, 8))
+    q2 = np.tile(np.array([3.0] + [0.0] * 7), (n, 1))
+    for j in range(16, 32):                                             # every key of block 1, so that each sampled line meets one
+        k2[j] = np.array([8.0] + [0.0] * 7)
+    sel = O.xa_select(q2, k2, stride, 0.9, blk)
+    for bi in range(2, nb):
+        assert set(np.nonzero(sel[bi])[0]) == {1, bi}

@@ -137,6 +137,25 @@ int flux_attn_prefill(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, co
                       int max_q_len, int max_kv_len, const flux_kv_cache* cache,
                       const uint8_t* mode, void* out, void* stream);
 
+/* Prefill attention of one layer with a BLOCK-SPARSE visible set for the sequences whose mode byte is 0 (Eq. 2
+ * over an arbitrary set of key blocks: the substrate of the sparse modes of Sec. 4.1 that choose blocks by content;
+ * a block of 64 positions is the minimum unit of sparsity, App. C.3).  Same arguments and conventions as
+ * flux_attn_prefill; cfg->n_sink, window and sa_block are not used.  A sequence with mode byte 1 runs FA.
+ *   block_mask: dev uint8 [batch, mask_heads, n_qblocks, n_kblocks], mask_heads = 1 (all heads share one matrix)
+ *               or n_q_heads.  Positions are grouped in blocks of 64.  For sequence b, row rq of its matrix belongs
+ *               to the query block  (kv_len[b] - n_q(b)) / 64 + rq  (row 0 is the block that holds its first query
+ *               of this call), column kb to key block kb.  Query position i sees key j iff j <= i and
+ *               (flag[block of i, block of j] != 0 or block of i == block of j): the causal order holds inside
+ *               blocks, and a query's own block is always kept.  Key blocks that no query block of a 128-row tile
+ *               keeps are not loaded.
+ *   n_kblocks * 64 >= max_kv_len and n_qblocks * 64 >= max_q_len, else FLUX_EINVAL.  A run of queries that starts
+ *   inside a block spans one block more than its length suggests: on the device, a pair that lies outside the
+ *   matrix counts as not kept and raises FLUX_DEV_BAD_LENGTH. */
+int flux_attn_prefill_blocksparse(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const int32_t* cu_q,
+                                  int max_q_len, int max_kv_len, const flux_kv_cache* cache, const uint8_t* mode,
+                                  const uint8_t* block_mask, int mask_heads, int n_qblocks, int n_kblocks, void* out,
+                                  void* stream);
+
 /* Decode attention of one layer: one query per sequence at position kv_len[b]-1 (append first).
  * q dev bf16 [batch, n_q_heads, head_dim]; out dev [batch, n_q_heads, head_dim].
  * FA streams all kv_len[b] cached rows; SA reads only rows [0, n_sink) and

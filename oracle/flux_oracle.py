@@ -171,18 +171,25 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mode: int, n_sink: in
 
 
 def attention_row(q_row: np.ndarray, k: np.ndarray, v: np.ndarray, i: int, mode: int, n_sink: int,
-                  window: int, scale: float | None = None, block: int = 1) -> np.ndarray:
+                  window: int, scale: float | None = None, block: int = 1, block_row=None,
+                  mask_block: int = BLOCK) -> np.ndarray:
     """One query position ``i`` of one KV-head group, predicate evaluated along the row.
 
     q_row [G, D] (the G query heads sharing this KV head), k and v [>= i+1, D].
     Returns [G, D].  Same definition as ``attention``; used where the mask
-    matrix would not fit.
+    matrix would not fit.  ``block_row`` (keep flags per key block, the row of a
+    block mask that belongs to position ``i``'s query block) selects the
+    block-sparse visible set instead of ``mode``.
     """
     d = q_row.shape[-1]
     if scale is None:
         scale = 1.0 / np.sqrt(d)
     j = np.arange(i + 1)
-    keep = visible(i, j, mode, n_sink, window, block)
+    if block_row is None:
+        keep = visible(i, j, mode, n_sink, window, block)
+    else:
+        bj = j // mask_block
+        keep = np.asarray(block_row, dtype=bool)[bj] | (bj == i // mask_block)
     kk = k[: i + 1][keep]
     vv = v[: i + 1][keep]
     s = scale * (q_row @ kk.T)                        # [G, n_visible]

@@ -26,7 +26,8 @@ FA, SA = 1, 0
 
 EXPORTS = ["flux_create", "flux_destroy", "flux_strerror", "flux_workspace_needed", "flux_last_device_status",
            "flux_router", "flux_kv_append", "flux_attn_prefill", "flux_attn_decode",
-           "flux_kv_append_ring", "flux_kv_compact_ring", "flux_attn_decode_ring", "flux_attn_decode_static"]
+           "flux_kv_append_ring", "flux_kv_compact_ring", "flux_attn_decode_ring", "flux_attn_decode_static",
+           "flux_attn_prefill_blocksparse"]
 STATIC_SCRATCH_BYTES = 16 * 1024 * 1024 + 256
 
 
@@ -61,6 +62,10 @@ _lib.flux_kv_append.restype = C.c_int
 _lib.flux_attn_prefill.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                    C.POINTER(FluxKVCache), C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.flux_attn_prefill.restype = C.c_int
+_lib.flux_attn_prefill_blocksparse.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                               C.POINTER(FluxKVCache), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                               C.c_void_p, C.c_void_p]
+_lib.flux_attn_prefill_blocksparse.restype = C.c_int
 _lib.flux_attn_decode.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_int, C.POINTER(FluxKVCache),
                                   C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.flux_attn_decode.restype = C.c_int
@@ -176,6 +181,14 @@ def flux_attn_prefill(ctx, cfg, q, cu_q, max_q_len, max_kv_len, cache, mode, out
     cs = _cache_struct(cache)
     _check(_lib.flux_attn_prefill(ctx, C.byref(cfg), _ptr(q), _ptr(cu_q), max_q_len, max_kv_len, C.byref(cs),
                                   _ptr(mode), _ptr(out), _stream(stream)))
+
+
+def flux_attn_prefill_blocksparse(ctx, cfg, q, cu_q, max_q_len, max_kv_len, cache, mode, block_mask, mask_heads,
+                                  n_qblocks, n_kblocks, out, stream=None) -> None:
+    cs = _cache_struct(cache)
+    _check(_lib.flux_attn_prefill_blocksparse(ctx, C.byref(cfg), _ptr(q), _ptr(cu_q), max_q_len, max_kv_len, C.byref(cs),
+                                              _ptr(mode), _ptr(block_mask), mask_heads, n_qblocks, n_kblocks, _ptr(out),
+                                              _stream(stream)))
 
 
 def flux_attn_decode(ctx, cfg, q, max_kv_len, cache, mode, out, stream=None) -> None:

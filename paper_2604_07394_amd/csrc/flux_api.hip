@@ -217,7 +217,31 @@ int flux_attn_prefill(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, co
   if (!aligned16(q) || !aligned16(out)) return FLUX_EINVAL;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
   const hipError_t e =
-      launch_prefill(ctx->c, *cfg, q, cu_q, max_q_len, max_kv_len, *cache, mode, out, (hipStream_t)stream);
+      launch_prefill(ctx->c, *cfg, q, cu_q, max_q_len, max_kv_len, *cache, mode, nullptr, out, (hipStream_t)stream);
+  return e == hipSuccess ? FLUX_OK : hip_fail(e);
+}
+
+int flux_attn_prefill_blocksparse(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const int32_t* cu_q,
+                                  int max_q_len, int max_kv_len, const flux_kv_cache* cache, const uint8_t* mode,
+                                  const uint8_t* block_mask, int mask_heads, int n_qblocks, int n_kblocks, void* out,
+                                  void* stream) {
+  if (!ctx || !q || !cu_q || !mode || !out || !block_mask) return FLUX_EINVAL;
+  int rc = check_cfg(cfg);
+  if (rc != FLUX_OK) return rc;
+  rc = check_cache(cache, cfg->head_dim);
+  if (rc != FLUX_OK) return rc;
+  if (max_q_len < 0 || max_kv_len < 0 || max_q_len > max_kv_len) return FLUX_EINVAL;
+  if (max_kv_len > cache->capacity) return FLUX_ECAPACITY;
+  if (!aligned16(q) || !aligned16(out)) return FLUX_EINVAL;
+  if (mask_heads != 1 && mask_heads != cfg->n_q_heads) return FLUX_EINVAL;
+  if (n_qblocks < 1 || n_kblocks < 1) return FLUX_EINVAL;
+  // the matrix must at least cover the bounds the caller states; whether it covers a run of queries that starts
+  // inside a block is seen on the device (FLUX_DEV_BAD_LENGTH)
+  if ((long long)n_kblocks * 64 < max_kv_len || (long long)n_qblocks * 64 < max_q_len) return FLUX_EINVAL;
+  if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
+  const BlockMask bm = {block_mask, mask_heads, n_qblocks, n_kblocks};
+  const hipError_t e =
+      launch_prefill(ctx->c, *cfg, q, cu_q, max_q_len, max_kv_len, *cache, mode, &bm, out, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
 }
 

@@ -79,9 +79,14 @@ size_t decode_partials_bytes(const flux_attn_cfg& cfg, const DecodePlan& p);
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
                          const flux_kv_cache& cache, const uint8_t* mode, int ring, void* out, hipStream_t s);
 
+// Keep flags of the block-sparse prefill: [batch, heads, n_qblocks, n_kblocks] bytes, heads = 1 or n_q_heads.
+struct BlockMask {
+  const uint8_t* flags;
+  int heads, n_qblocks, n_kblocks;
+};
 hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q, const int32_t* cu_q,
                           int max_q_len, int max_kv_len, const flux_kv_cache& cache, const uint8_t* mode,
-                          void* out, hipStream_t s);
+                          const BlockMask* bm /*nullptr: the sink + window form*/, void* out, hipStream_t s);
 
 hipError_t launch_router(const Ctx& c, const void* x, const int32_t* cu_seqlens, int batch, int hidden, int pool,
                          const void* w1, const void* b1, const void* w2, const void* b2, int inner,

@@ -18,6 +18,12 @@
 // random bf16 data reaches 2030-2280 TFLOP/s with it and 1170-1450 with 32x32x16, whatever the number of
 // independent accumulators.
 // Only blocks that straddle the causal diagonal or a window / sink edge evaluate the element mask.
+//
+// flux_attn_prefill_blocksparse is the same kernel (template flag BS) with another list of visited blocks: a
+// sequence whose mode byte is 0 visits the key blocks that a caller-given keep matrix marks for the query
+// blocks of the workgroup's tile (Eq. 2 over an arbitrary set of 64-position blocks, App. C.3: the block is
+// the minimum unit of sparsity), found by scanning the matrix 64 key blocks at a time; blocks that no row of
+// the tile keeps are never loaded.
 #include <type_traits>
 
 #include "flux_internal.h"
@@ -41,6 +47,10 @@ struct PrefillArgs {
   int out_fp32;
   void* out;
   uint32_t* status;       // sticky device status word
+  // block-sparse form only: keep flags [batch, bm_heads, bm_qblocks, bm_kblocks], one byte per (query block, key
+  // block) pair of 64 x 64 positions; row 0 is the block that holds the call's first query of that sequence
+  const uint8_t* bmask;
+  int bm_heads, bm_qblocks, bm_kblocks;
 };
 
 constexpr int BM = 128;   // query rows per workgroup
@@ -82,7 +92,7 @@ __device__ __forceinline__ void dma_tile2(const char* kt, const char* vt, const 
                : "memory", "m0", "scc");
 }
 
-template <int D>
+template <int D, bool BS>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int BN = 64;                  // keys per iteration: two halves of 32, the K dimension of one PV MFMA
   constexpr int KC = D / 32;              // MFMA k-steps over the head dimension (QK^T)
@@ -242,8 +252,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 
   // All transfers of one tile with rows clamped to the cached length: the first tile, and a last tile that
   // is only partly inside the cache.
-  auto issue_tile_clamped = [&](int it, int stage) {
-    const int j0 = tile_of(it) * BN;
+  auto issue_tile_clamped = [&](int tile, int stage) {
+    const int j0 = tile * BN;
     const int rmax = len - 1 - j0;                           // rows past the cached length are clamped
     const char* kt = kbase + (int64_t)j0 * pitch_g;
     const char* vt = vbase + (int64_t)j0 * pitch_g;
@@ -308,22 +318,92 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   const char* kt_n = kbase + (int64_t)(n_iter > 1 ? tile_of(1) : 0) * step_b;   // the tile the next transfer brings in
   const char* vt_n = vbase + (int64_t)(n_iter > 1 ? tile_of(1) : 0) * step_b;
 
+  // ---- block-sparse form: the visited key blocks come from the keep matrix.  The tile's 128 rows lie in up
+  // to three 64-position query blocks (two when the first query sits on a block boundary); a key block is
+  // visited when any of them keeps it.  The matrix is scanned 64 key blocks at a time: lane l of every wave reads
+  // the flag of key block win + l for each of the tile's query blocks, a ballot turns them into one 64-bit word
+  // per query block, and the blocks are taken from the lowest set bit up.  Every wave runs the same scan (all of
+  // it in scalar registers), so no exchange is needed.  A query block always keeps its own (diagonal) block, and
+  // never a later one; an FA sequence (mode byte 1) keeps everything.
+  const int rb0 = i_tile_min >> 6;                           // absolute index of the tile's first query block
+  const int n_rb = (i_tile_max >> 6) - rb0 + 1;              // 1 .. 3
+  int scan_win = -64;                                        // first key block of the 64 being scanned
+  unsigned long long scan_bits[3] = {0, 0, 0};               // what is left of them, per query block of the tile
+  int cur_kb = -1, cur_rows = 0;                             // the block of this iteration, and which query blocks keep it
+  const uint8_t* bm_seq = nullptr;
+  if constexpr (BS) {
+    if (sa) bm_seq = a.bmask + ((int64_t)b * a.bm_heads + (a.bm_heads > 1 ? h : 0)) * a.bm_qblocks * (int64_t)a.bm_kblocks;
+  }
+  auto next_kept_block = [&](int& rows) -> int {
+    for (;;) {
+      const unsigned long long any = scan_bits[0] | scan_bits[1] | scan_bits[2];
+      if (any != 0) {
+        const int bit = __builtin_ctzll(any);
+        rows = (int)((scan_bits[0] >> bit) & 1) | (int)(((scan_bits[1] >> bit) & 1) << 1) | (int)(((scan_bits[2] >> bit) & 1) << 2);
+        const unsigned long long clr = ~(1ull << bit);
+        scan_bits[0] &= clr;
+        scan_bits[1] &= clr;
+        scan_bits[2] &= clr;
+        return scan_win + bit;
+      }
+      scan_win += 64;
+      if (scan_win > last_blk) return -1;
+      const int kbk = scan_win + l;
+#pragma unroll
+      for (int r = 0; r < 3; ++r) {
+        const int rb = rb0 + r;                              // absolute query block
+        bool keep = r < n_rb && kbk <= rb;                   // never a later block (causal), nothing for absent rows
+        if (keep && kbk < rb && bm_seq != nullptr) {         // the diagonal block is kept whatever the flag says
+          const int rq = rb - (pos0 >> 6);
+          // a matrix too small for the lengths found on the device hides what it does not cover, and says so
+          const bool inside = rq < a.bm_qblocks && kbk < a.bm_kblocks;
+          if (!inside && w == 0 && h == 0) atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
+          keep = inside && bm_seq[(int64_t)rq * a.bm_kblocks + kbk] != 0;
+        }
+        scan_bits[r] = __builtin_amdgcn_ballot_w64(keep);
+      }
+    }
+  };
+  int nxt_kb = -1, nxt_rows = 0;
+
   // One iteration.  STG (the LDS stage of this tile) is a compile-time constant: the loop is unrolled by two so
   // that every LDS address is a loop-invariant register plus an immediate.
   auto iteration = [&](int it, auto stg_c) {
     constexpr int STG = decltype(stg_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this wave's transfers have landed
     __syncthreads();                                         // ... and everyone's; the other stage is free
-    if (it + 1 < lim_whole) {                                // the next tile, in flight during the math below
+    if constexpr (BS) {
+      nxt_kb = next_kept_block(nxt_rows);
+      if (nxt_kb >= 0) {                                     // the next kept block, in flight during the math below
+        if ((nxt_kb + 1) * BN <= len) {
+          const int64_t off = (int64_t)nxt_kb * step_b;
+          if constexpr (KPW == 4) dma_tile4<(STG ^ 1) * STAGE, KTILE>(kbase + off, vbase + off, k_off, v_off, lds_w);
+          else dma_tile2<(STG ^ 1) * STAGE, KTILE>(kbase + off, vbase + off, k_off, v_off, lds_w);
+        } else {
+          issue_tile_clamped(nxt_kb, STG ^ 1);
+        }
+      }
+    } else if (it + 1 < lim_whole) {                         // the next tile, in flight during the math below
       if constexpr (KPW == 4) dma_tile4<(STG ^ 1) * STAGE, KTILE>(kt_n, vt_n, k_off, v_off, lds_w);
       else dma_tile2<(STG ^ 1) * STAGE, KTILE>(kt_n, vt_n, k_off, v_off, lds_w);
       const int64_t adv = it + 2 == n_a ? jump_b : step_b;   // on to the tile after it (the window part starts at win0)
       kt_n += adv;
       vt_n += adv;
     } else if (it + 1 < n_iter) {
-      issue_tile_clamped(it + 1, STG ^ 1);                   // a last tile that is only partly inside the cache
+      issue_tile_clamped(tile_of(it + 1), STG ^ 1);          // a last tile that is only partly inside the cache
     }
-    const bool plain = it < pa_end || (unsigned)(it - pb_begin) < pb_len;
+    bool plain = it < pa_end || (unsigned)(it - pb_begin) < pb_len;
+    // block-sparse form: this block (cur_kb) as the wave's rows see it.  The wave's 32 rows lie in one or two of
+    // the tile's query blocks; the block is plain when both keep it and it ends at or before the wave's first row.
+    const int bs_j0 = cur_kb * BN, bs_rows = cur_rows;
+    if constexpr (BS) {
+      const int r_lo = (i_w_min >> 6) - rb0, r_hi = (max(i_w_max, i_w_min) >> 6) - rb0;
+      const bool k_lo = (bs_rows >> r_lo) & 1, k_hi = (bs_rows >> r_hi) & 1;
+      plain = wave_active && k_lo && k_hi && bs_j0 + BN - 1 <= i_w_min;
+      cur_kb = nxt_kb;                                       // the state moves on; this iteration keeps bs_j0 / bs_rows
+      cur_rows = nxt_rows;
+      if (!plain && (!wave_active || bs_j0 > i_w_max || !(k_lo || k_hi))) return;   // nothing for this wave here
+    }
 
     FLUX_LDS char* st = (FLUX_LDS char*)smem + STG * STAGE;
     // Order of the block, written out so that every LDS read is issued well before its use (the fences keep
@@ -429,7 +509,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     // block's first key and the mask flags; a plain block needs none of that scalar work
     int j0 = 0;
     bool mask_causal = false, mask_edge = false;
-    if (!plain) {
+    if constexpr (BS) {
+      j0 = bs_j0;
+      mask_causal = !plain;
+    } else if (!plain) {
       j0 = tile_of(it) * BN;
       bool skip = !wave_active || j0 > i_w_max;
       mask_causal = j0 + BN - 1 > i_w_min;                   // the diagonal crosses the block
@@ -469,7 +552,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     } else if (mask_causal) {
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        const int hi = i_mine[qb] - j0 - 4 * g;
+        int hi = i_mine[qb] - j0 - 4 * g;
+        // block-sparse form: a row whose query block does not keep this key block sees none of it
+        if constexpr (BS) hi = ((bs_rows >> ((i_mine[qb] >> 6) - rb0)) & 1) ? hi : -1;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -485,10 +570,20 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     accumulate(1);
   };
 
-  if (n_iter > 0) issue_tile_clamped(0, 0);
-  for (int it = 0; it < n_iter; it += 2) {
-    iteration(it, std::integral_constant<int, 0>());
-    if (it + 1 < n_iter) iteration(it + 1, std::integral_constant<int, 1>());
+  if constexpr (!BS) {
+    if (n_iter > 0) issue_tile_clamped(tile_of(0), 0);
+    for (int it = 0; it < n_iter; it += 2) {
+      iteration(it, std::integral_constant<int, 0>());
+      if (it + 1 < n_iter) iteration(it + 1, std::integral_constant<int, 1>());
+    }
+  } else {
+    cur_kb = next_kept_block(cur_rows);
+    if (cur_kb >= 0) issue_tile_clamped(cur_kb, 0);
+    while (cur_kb >= 0) {
+      iteration(0, std::integral_constant<int, 0>());
+      if (cur_kb < 0) break;
+      iteration(0, std::integral_constant<int, 1>());
+    }
   }
 
   // ---- normalise and store: lane (n, g) holds d = 16*db + 4*g .. +3 of its two query rows
@@ -517,7 +612,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 
 hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q, const int32_t* cu_q,
                           int max_q_len, int max_kv_len, const flux_kv_cache& cache, const uint8_t* mode,
-                          void* out, hipStream_t s) {
+                          const BlockMask* bm, void* out, hipStream_t s) {
   (void)max_kv_len;
   const float scale = cfg.softmax_scale != 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.head_dim);
   PrefillArgs a;
@@ -544,6 +639,10 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.out_fp32 = cfg.out_dtype;
   a.out = out;
   a.status = c.status;
+  a.bmask = bm ? bm->flags : nullptr;
+  a.bm_heads = bm ? bm->heads : 0;
+  a.bm_qblocks = bm ? bm->n_qblocks : 0;
+  a.bm_kblocks = bm ? bm->n_kblocks : 0;
   if (a.n_qtiles == 0) return hipSuccess;
   const long long n_pairs = (long long)cache.batch * cfg.n_kv_heads;
   long long n_wg;
@@ -560,8 +659,13 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   }
   if (n_wg > 0x7FFFFFFFll) return hipErrorInvalidValue;
   const dim3 grid((unsigned)n_wg);
-  if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((prefill_kernel<64>), grid, dim3(256), 0, s, a);
+  if (bm) {
+    if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((prefill_kernel<64, true>), grid, dim3(256), 0, s, a);
+  } else {
+    if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, false>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((prefill_kernel<64, false>), grid, dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 

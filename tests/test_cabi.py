@@ -171,3 +171,23 @@ def test_window_and_sinks_near_the_largest_int_do_not_wrap(F, nodev):
         assert rc_of(F, F.flux_attn_decode_ring, nodev, F.attn_cfg(8, 2, 128, 4, big, 0.0, 0, blk), 4096, kc, 1024) == F.FLUX_ECAPACITY
         assert rc_of(F, F.flux_attn_decode_ring, nodev, F.attn_cfg(8, 2, 128, big, 16, 0.0, 0, blk), 4096, kc, 1024) == F.FLUX_ECAPACITY
         assert F.flux_workspace_needed(F.attn_cfg(8, 2, 128, big, big, 0.0, 0, blk), 2, 4096) > 0
+
+
+def test_blocksparse_argument_validation(F, nodev):
+    good = F.attn_cfg(8, 2, 128, 0, 1)
+    kc = cache_struct(F)
+    call = lambda **kw: rc_of(F, F.flux_attn_prefill_blocksparse, nodev, kw.get("cfg", good), 4096, 768, kw.get("mq", 32),
+                              kw.get("mk", 64), kc, 512, kw.get("mask", 2048), kw.get("heads", 1), kw.get("nq", 2),
+                              kw.get("nk", 1), 1024)
+    assert call() == F.FLUX_EHIP                                   # 32 queries somewhere in a 64-position cache
+    assert call(nq=1) == F.FLUX_EHIP                               # (whether they span two blocks is seen on the device)
+    assert call(mq=64, mk=64, nq=0) == F.FLUX_EINVAL
+    assert call(mask=None) == F.FLUX_EINVAL
+    assert call(heads=3) == F.FLUX_EINVAL                          # one matrix for all heads, or one per query head
+    assert call(heads=8) == F.FLUX_EHIP
+    assert call(nk=0) == F.FLUX_EINVAL
+    assert call(mq=64, mk=64, nq=1, nk=1) == F.FLUX_EHIP           # a whole prompt: the queries start on a block boundary
+    assert call(mq=64, mk=64, nq=1, nk=1) == F.FLUX_EHIP
+    assert call(mk=64, nk=1) == F.FLUX_EHIP
+    assert call(mk=65, nk=1) == F.FLUX_ECAPACITY                   # beyond the cache capacity of the fixture
+    assert call(cfg=F.attn_cfg(8, 3, 128, 0, 1)) == F.FLUX_EINVAL

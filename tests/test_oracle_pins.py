@@ -468,6 +468,17 @@ def test_block_sparse_attention_matches_brute_force(n_q, n_kv):
         assert np.array_equal(got_h[:, h], one[:, h])
 
 
+def test_block_sparse_row_form_matches_matrix_form():
+    blk, n = 4, 37
+    q, k, v = make_qkv(65, n, n, 3, 1, 5)
+    nb = -(-n // blk)
+    bm = rng(66).random((nb, nb)) < 0.35
+    full = O.attention(q, k, v, FA, 0, 1, block_mask=bm, mask_block=blk)
+    for i in (0, 3, 4, 17, 36):
+        row = O.attention_row(q[i], k[:, 0], v[:, 0], i, FA, 0, 1, block_row=bm[i // blk], mask_block=blk)
+        assert np.abs(row - full[i]).max() < 1e-13
+
+
 def test_block_mask_all_true_is_fa_and_sink_window_blocks_are_block_granular_sa():
     blk, n = 8, 100
     q, k, v = make_qkv(64, n, n, 4, 2, 8)

@@ -156,6 +156,28 @@ int flux_attn_prefill_blocksparse(flux_ctx* ctx, const flux_attn_cfg* cfg, const
                                   const uint8_t* block_mask, int mask_heads, int n_qblocks, int n_kblocks, void* out,
                                   void* stream);
 
+/* Block selection of the XA sparse mode (Sec. 4.1; Table 3: stride 16, threshold 0.9, selection mode "Inverse",
+ * block 64) for whole prompts: writes, for every sequence and query head, the keep matrix that
+ * flux_attn_prefill_blocksparse consumes (mask_heads = n_q_heads).  The paper gives the method's name ("Block
+ * Sparse Attention with Antidiagonal Scoring") and these parameters, nothing more; what is computed is this reading:
+ *   - the scaled scores of a head are cut into squares of stride x stride positions; of a square only the
+ *     antidiagonal is sampled (query offset r against key offset stride-1-r: the "Inverse" order), and only the
+ *     causal samples inside the prompt; e[a][b] = the mean of the samples of square (a, b);
+ *   - softmax over every row a of e (its squares b <= a);
+ *   - mass of a block pair = the sum of those probabilities inside it / the rows of e the query block has;
+ *   - query block I keeps every key block whose mass is at least the mass of the block at which the masses, taken
+ *     in descending order, first reach `threshold` (equal masses are kept together), and always its own block.
+ * q, cu_q, cache as in flux_attn_prefill, with n_q(b) == kv_len[b] for every sequence (a whole prompt, appended
+ * first; anything else raises FLUX_DEV_BAD_LENGTH and scores the first min(n_q, kv_len) positions).  stride must be
+ * 16; 0 < threshold <= 1; cfg->softmax_scale as in Eq. 1; cfg->n_sink, window, sa_block, out_dtype are not used.
+ * block_mask: dev uint8 [batch, n_q_heads, n_qblocks, n_kblocks], every byte written (0 or 1);
+ * n_kblocks * 64 >= max_kv_len, n_qblocks * 64 >= max_q_len, n_kblocks <= 4096 (262144 positions), else FLUX_EINVAL.
+ * The masses are computed in fp32 from exact bf16 products: near a tie between the threshold and a partial sum
+ * of masses the selection can differ from one made in higher precision. */
+int flux_xa_select(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const int32_t* cu_q, int max_q_len,
+                   int max_kv_len, const flux_kv_cache* cache, int stride, float threshold, uint8_t* block_mask,
+                   int n_qblocks, int n_kblocks, void* stream);
+
 /* Decode attention of one layer: one query per sequence at position kv_len[b]-1 (append first).
  * q dev bf16 [batch, n_q_heads, head_dim]; out dev [batch, n_q_heads, head_dim].
  * FA streams all kv_len[b] cached rows; SA reads only rows [0, n_sink) and

@@ -309,7 +309,8 @@ def compact_to_ring(full: KVCache, ring: RingKVCache) -> None:
 
 # --------------------------------------------------------------------------- XAttention block selection
 
-def xa_block_mass(q: np.ndarray, k: np.ndarray, stride: int = 16, block: int = BLOCK, scale: float | None = None):
+def xa_block_mass(q: np.ndarray, k: np.ndarray, stride: int = 16, block: int = BLOCK, scale: float | None = None,
+                  blocks=None):
     """Approximate attention mass of every (query block, key block) pair of ONE head from antidiagonal samples.
 
     The reading taken of "Block Sparse Attention with Antidiagonal Scoring", stride 16, selection mode
@@ -330,55 +331,49 @@ def xa_block_mass(q: np.ndarray, k: np.ndarray, stride: int = 16, block: int = B
        query block has, so that the masses of one query block sum to one.
 
     Returns ``mass`` [n_qblocks, n_kblocks] (fp64; zero above the block diagonal).  ``n`` need not be a
-    multiple of ``block`` or ``stride``: trailing positions form shorter squares and blocks.
+    multiple of ``block`` or ``stride``: trailing positions form shorter squares and blocks.  ``blocks``
+    (query block indices) limits the work to those rows of the result; the others stay zero.
     """
     n, d = q.shape
     assert k.shape == (n, d) and block % stride == 0
     if scale is None:
         scale = 1.0 / np.sqrt(d)
     n_sq = -(-n // stride)
-    e = np.full((n_sq, n_sq), -np.inf)
-    s = scale * (q @ k.T)
-    for a in range(n_sq):
-        for b in range(a + 1):
-            tot, cnt = 0.0, 0
-            for r in range(stride):
-                i, j = stride * a + r, stride * b + stride - 1 - r
-                if i < n and j < n and j <= i:
-                    tot += s[i, j]
-                    cnt += 1
-            if cnt:
-                e[a, b] = tot / cnt
-    p = np.zeros_like(e)
-    for a in range(n_sq):
-        row = e[a, : a + 1]
-        ok = np.isfinite(row)
-        w = np.exp(row[ok] - row[ok].max())
-        p[a, : a + 1][ok] = w / w.sum()
     per = block // stride
     n_blk = -(-n // block)
     mass = np.zeros((n_blk, n_blk))
-    for bi in range(n_blk):
-        rows = p[per * bi: per * (bi + 1)]
-        for bj in range(bi + 1):
-            mass[bi, bj] = rows[:, per * bj: per * (bj + 1)].sum() / rows.shape[0]
+    r = np.arange(stride)
+    for bi in (range(n_blk) if blocks is None else blocks):
+        rows_a = range(per * bi, min(per * (bi + 1), n_sq))          # the rows of e this query block has
+        for a in rows_a:
+            i = stride * a + r                                      # query positions of square row a, one per offset
+            j = stride * np.arange(a + 1)[None, :] + (stride - 1 - r)[:, None]   # their antidiagonal partners, per square
+            ok = (i[:, None] < n) & (j < n) & (j <= i[:, None])     # inside the prompt and causal
+            ic, jc = np.minimum(i, n - 1), np.minimum(j, n - 1)
+            smp = scale * np.einsum("rd,rbd->rb", q[ic], k[jc])     # the sampled scores, [offset, square]
+            cnt = ok.sum(axis=0)
+            e = np.where(cnt > 0, np.where(ok, smp, 0.0).sum(axis=0) / np.maximum(cnt, 1), -np.inf)
+            w = np.where(cnt > 0, np.exp(e - e[cnt > 0].max()), 0.0)
+            p = w / w.sum()                                         # softmax over the squares of row a
+            for bj in range(bi + 1):
+                mass[bi, bj] += p[per * bj: per * (bj + 1)].sum() / len(rows_a)
     return mass
 
 
 def xa_select(q: np.ndarray, k: np.ndarray, stride: int = 16, threshold: float = 0.9, block: int = BLOCK,
-              scale: float | None = None, return_mass: bool = False):
+              scale: float | None = None, return_mass: bool = False, blocks=None):
     """Key blocks every query block of ONE head keeps (Table 3: threshold 0.9).
 
     For query block I the key blocks are taken in descending order of ``xa_block_mass`` until the masses
     taken reach ``threshold``; every block whose mass equals that of the last one taken is kept as well (so
     the result does not depend on how equal masses are ordered).  The diagonal block (the queries' own
     positions) is always kept.  Returns a boolean matrix [n_qblocks, n_kblocks] to be used as the
-    ``block_mask`` of ``attention``.
+    ``block_mask`` of ``attention`` (only the rows ``blocks`` if given; the others stay empty).
     """
-    mass = xa_block_mass(q, k, stride, block, scale)
+    mass = xa_block_mass(q, k, stride, block, scale, blocks)
     n_blk = mass.shape[0]
     keep = np.zeros((n_blk, n_blk), dtype=bool)
-    for bi in range(n_blk):
+    for bi in (range(n_blk) if blocks is None else blocks):
         m = mass[bi, : bi + 1]
         order = np.argsort(-m, kind="stable")
         csum = np.cumsum(m[order])

@@ -27,7 +27,7 @@ FA, SA = 1, 0
 EXPORTS = ["flux_create", "flux_destroy", "flux_strerror", "flux_workspace_needed", "flux_last_device_status",
            "flux_router", "flux_kv_append", "flux_attn_prefill", "flux_attn_decode",
            "flux_kv_append_ring", "flux_kv_compact_ring", "flux_attn_decode_ring", "flux_attn_decode_static",
-           "flux_attn_prefill_blocksparse"]
+           "flux_attn_prefill_blocksparse", "flux_xa_select"]
 STATIC_SCRATCH_BYTES = 16 * 1024 * 1024 + 256
 
 
@@ -66,6 +66,9 @@ _lib.flux_attn_prefill_blocksparse.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg
                                                C.POINTER(FluxKVCache), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                                C.c_void_p, C.c_void_p]
 _lib.flux_attn_prefill_blocksparse.restype = C.c_int
+_lib.flux_xa_select.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                C.POINTER(FluxKVCache), C.c_int, C.c_float, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+_lib.flux_xa_select.restype = C.c_int
 _lib.flux_attn_decode.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_int, C.POINTER(FluxKVCache),
                                   C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.flux_attn_decode.restype = C.c_int
@@ -189,6 +192,13 @@ def flux_attn_prefill_blocksparse(ctx, cfg, q, cu_q, max_q_len, max_kv_len, cach
     _check(_lib.flux_attn_prefill_blocksparse(ctx, C.byref(cfg), _ptr(q), _ptr(cu_q), max_q_len, max_kv_len, C.byref(cs),
                                               _ptr(mode), _ptr(block_mask), mask_heads, n_qblocks, n_kblocks, _ptr(out),
                                               _stream(stream)))
+
+
+def flux_xa_select(ctx, cfg, q, cu_q, max_q_len, max_kv_len, cache, stride, threshold, block_mask, n_qblocks, n_kblocks,
+                   stream=None) -> None:
+    cs = _cache_struct(cache)
+    _check(_lib.flux_xa_select(ctx, C.byref(cfg), _ptr(q), _ptr(cu_q), max_q_len, max_kv_len, C.byref(cs), stride,
+                               threshold, _ptr(block_mask), n_qblocks, n_kblocks, _stream(stream)))
 
 
 def flux_attn_decode(ctx, cfg, q, max_kv_len, cache, mode, out, stream=None) -> None:

@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "lib")
 COMMON = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
-FLUX_SOURCES = ["flux_api.hip", "kv_append.hip", "decode.hip", "prefill.hip", "router.hip"]
+FLUX_SOURCES = ["flux_api.hip", "kv_append.hip", "decode.hip", "prefill.hip", "router.hip", "xa_select.hip"]
 
 
 def _run(cmd):

@@ -245,6 +245,28 @@ int flux_attn_prefill_blocksparse(flux_ctx* ctx, const flux_attn_cfg* cfg, const
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
 }
 
+int flux_xa_select(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const int32_t* cu_q, int max_q_len,
+                   int max_kv_len, const flux_kv_cache* cache, int stride, float threshold, uint8_t* block_mask,
+                   int n_qblocks, int n_kblocks, void* stream) {
+  if (!ctx || !q || !cu_q || !block_mask) return FLUX_EINVAL;
+  int rc = check_cfg(cfg);
+  if (rc != FLUX_OK) return rc;
+  rc = check_cache(cache, cfg->head_dim);
+  if (rc != FLUX_OK) return rc;
+  if (stride != 16) return FLUX_EINVAL;                             // the stride of Table 3 is the one built
+  if (!(threshold > 0.f) || !(threshold <= 1.f)) return FLUX_EINVAL;
+  if (max_q_len < 0 || max_kv_len < 0 || max_q_len > max_kv_len) return FLUX_EINVAL;
+  if (max_kv_len > cache->capacity) return FLUX_ECAPACITY;
+  if (!aligned16(q)) return FLUX_EINVAL;
+  if (n_qblocks < 1 || n_kblocks < 1 || n_kblocks > kXaMaxKBlocks) return FLUX_EINVAL;
+  if ((long long)n_kblocks * 64 < max_kv_len || (long long)n_qblocks * 64 < max_q_len) return FLUX_EINVAL;
+  if (cfg->n_q_heads > 65535 || cache->batch > 65535) return FLUX_EINVAL;
+  if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
+  const hipError_t e = launch_xa_select(ctx->c, *cfg, q, cu_q, max_q_len, *cache, threshold, block_mask, n_qblocks,
+                                        n_kblocks, (hipStream_t)stream);
+  return e == hipSuccess ? FLUX_OK : hip_fail(e);
+}
+
 int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int max_kv_len,
                      const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream) {
   if (!ctx || !q || !mode || !out) return FLUX_EINVAL;

@@ -88,6 +88,13 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
                           int max_q_len, int max_kv_len, const flux_kv_cache& cache, const uint8_t* mode,
                           const BlockMask* bm /*nullptr: the sink + window form*/, void* out, hipStream_t s);
 
+// XA block selection: LDS of one workgroup (partial tiles + the masses of 4 query blocks), and the launcher
+constexpr int kXaMaxKBlocks = 4096;           // key blocks a prompt may have (262144 positions): the masses live in LDS
+inline size_t xa_select_lds_bytes(int n_kblocks) { return (size_t)2 * 4 * 256 * 4 + (size_t)4 * n_kblocks * 4; }
+hipError_t launch_xa_select(const Ctx& c, const flux_attn_cfg& cfg, const void* q, const int32_t* cu_q, int max_q_len,
+                            const flux_kv_cache& cache, float threshold, uint8_t* mask, int n_qblocks, int n_kblocks,
+                            hipStream_t s);
+
 hipError_t launch_router(const Ctx& c, const void* x, const int32_t* cu_seqlens, int batch, int hidden, int pool,
                          const void* w1, const void* b1, const void* w2, const void* b2, int inner,
                          uint8_t* mode_out, float* logits_out, hipStream_t s);

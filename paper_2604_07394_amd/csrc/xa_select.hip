@@ -1,0 +1,280 @@
+// flux_xa_select: the key blocks each query block of a prompt keeps under the XA sparse mode (Sec. 4.1; Table 3:
+// stride 16, threshold 0.9, selection mode "Inverse", block 64), written as the keep matrix that
+// flux_attn_prefill_blocksparse consumes.  The paper names the method ("Block Sparse Attention with
+// Antidiagonal Scoring") and its parameters only; what is computed is this reading of them:
+//
+//   1. The scaled score matrix of one head is cut into squares of 16 x 16 positions.  Of square (a, b) only the
+//      antidiagonal is looked at (query row offset r against key column offset 15 - r: the rows taken in inverse
+//      order against the columns), and of it only the causal samples inside the prompt; e[a][b] is their mean.
+//   2. Every row a of e becomes probabilities over its squares b <= a by a softmax.
+//   3. The mass of block pair (I, J) is the sum of those probabilities over its 4 x 4 squares divided by the rows
+//      of e the query block has; the masses of a query block sum to one.
+//   4. Query block I keeps every key block whose mass is at least that of the block at which the masses, taken
+//      in descending order, first reach the threshold; and always its own block.
+//
+// Step 1 is a matrix product over 16 * D numbers per square: the 16 query rows of square row a laid end to end
+// against the 16 key rows of square column b laid end to end in inverse order.  One workgroup owns 16 square
+// rows (256 queries, 4 query blocks) of one head and walks the square columns 16 at a time (256 keys):
+//   - the contraction is split over the four waves by the row offset r (wave w takes r = 4w .. 4w+3), so each
+//     wave keeps its share of the query operand in registers for the whole kernel and loads only its share of
+//     every key tile, straight from global memory in MFMA operand layout (16x16x32 bf16, S^T = K Q^T);
+//   - the four partial 16 x 16 tiles meet in LDS, where thread (a, b) adds them in wave order.  On the diagonal
+//     the samples r < 8 are not causal: exactly the partial tiles of waves 0 and 1, which are left out there;
+//     positions past the prompt are zeroed in the operands, and the number of samples of a square is a closed form;
+//   - the softmax over a row of squares needs the row's maximum and sum first, so the columns are walked twice:
+//     once for (max, sum), once for the probabilities, which are summed 4 x 4 into the masses (a wave of the
+//     reduction phase holds the 4 square rows of one query block);
+//   - the threshold is found without sorting: the largest mass value t with sum(mass >= t) >= threshold * total,
+//     by bisection over the bit patterns of the positive floats (32 steps, one row reduction each).
+#include <type_traits>
+
+#include "flux_internal.h"
+
+namespace flux {
+
+struct XaArgs {
+  const __bf16* q;        // [T, Hq, D]
+  const int32_t* cu_q;    // [B + 1]
+  const __bf16* k;
+  int64_t stride_b, stride_h, stride_t;   // elements
+  const int32_t* kv_len;
+  int capacity;
+  int hq, group;
+  float scale;            // softmax scale (not in log2 units)
+  float threshold;
+  uint8_t* mask;          // [B, Hq, n_qblocks, n_kblocks]
+  int n_qblocks, n_kblocks;
+  uint32_t* status;
+};
+
+constexpr int kXaRows = 16;        // square rows per workgroup (256 queries)
+constexpr int kXaStride = 16;      // positions per square side (Table 3: stride 16)
+
+template <int D>
+__global__ __launch_bounds__(256) void xa_select_kernel(XaArgs a) {
+  constexpr int ST = D / 8;        // k-steps of 32 numbers per wave: 4 row offsets x D / 32
+  constexpr int SPR = D / 32;      // k-steps per row offset
+  extern __shared__ __attribute__((aligned(16))) char xa_smem[];
+  float* part = (float*)xa_smem;                       // [2 buffers][4 waves][16 a][16 b]
+  float* mass = part + 2 * 4 * 256;                    // [4 query blocks][n_kblocks]
+
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
+  const int g = l >> 4, nn = l & 15;
+  const int grp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int kvh = h / a.group;
+
+  const int q_begin = a.cu_q[b];
+  const int n_q = a.cu_q[b + 1] - q_begin;
+  int len = a.kv_len[b];
+  // the selection is defined for a whole prompt: as many queries as cached positions
+  if (grp == 0 && h == 0 && tid == 0 && (len < 0 || len > a.capacity || n_q != len)) atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
+  len = len < 0 ? 0 : (len > a.capacity ? a.capacity : len);
+  const int n = n_q < len ? (n_q < 0 ? 0 : n_q) : len;   // positions 0 .. n-1 are scored
+  const int a0 = grp * kXaRows;                          // first square row of the workgroup
+  uint8_t* mrow0 = a.mask + (((int64_t)b * a.hq + h) * a.n_qblocks + 4 * grp) * (int64_t)a.n_kblocks;
+  const int n_sq = (n + kXaStride - 1) / kXaStride;      // square rows / columns of the prompt
+  if (a0 >= n_sq) {                                      // nothing to score: the rows of the matrix are cleared
+    for (int qb = 0; qb < 4; ++qb)
+      if (4 * grp + qb < a.n_qblocks)
+        for (int j = tid; j < a.n_kblocks; j += 256) mrow0[(int64_t)qb * a.n_kblocks + j] = 0;
+    return;
+  }
+  const int a_last = min(a0 + kXaRows, n_sq) - 1;        // last existing square row of the workgroup
+  const int n_ct = a_last / 16 + 1;                      // column tiles (16 square columns each) to walk
+
+  // ---- query operand of this wave: lane (nn, g) holds, for k-step st, 8 numbers of query row 16*(a0+nn) + r,
+  // r = 4w + st / SPR, d = 32 * (st % SPR) + 8g; rows past the prompt are zero
+  bf16x8 qf[ST];
+  {
+    const u32x4 zero = {0, 0, 0, 0};
+#pragma unroll
+    for (int st = 0; st < ST; ++st) {
+      const int r = 4 * w + st / SPR, d = 32 * (st % SPR) + 8 * g;
+      const int pos = kXaStride * (a0 + nn) + r;
+      const int pc = pos < n ? pos : (n > 0 ? n - 1 : 0);
+      const u32x4 t = *(const u32x4*)(a.q + ((int64_t)(q_begin + pc) * a.hq + h) * D + d);
+      qf[st] = __builtin_bit_cast(bf16x8, pos < n ? t : zero);
+    }
+  }
+  const __bf16* kbase = a.k + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
+
+  // One column tile: the key operand of this wave is fetched one tile ahead (the fetch of tile ct + 1 is issued
+  // before the products of tile ct, so a whole tile's work covers its latency); partial sums go to part[buf][w].
+  // Keys past the prompt (only the last tile can hold any) are fetched from a clamped address and zeroed when
+  // they are used, not when they are fetched: a select behind the load would wait for it at once.
+  u32x4 kreg[2][ST];
+  auto key_of = [&](int ct, int st) __attribute__((always_inline)) { return kXaStride * (16 * ct + nn) + (kXaStride - 1) - (4 * w + st / SPR); };
+  auto fetch_tile = [&](int ct, auto set_c) __attribute__((always_inline)) {                // the register set is a compile-time constant
+    constexpr int set = decltype(set_c)::value;
+#pragma unroll
+    for (int st = 0; st < ST; ++st) {
+      const int key = key_of(ct, st);                        // key row of square column 16*ct + nn, inverse order
+      const int kc = key < n ? key : (n > 0 ? n - 1 : 0);
+      kreg[set][st] = *(const u32x4*)(kbase + (int64_t)kc * a.stride_t + 32 * (st % SPR) + 8 * g);
+    }
+  };
+  auto partial_tile = [&](int ct, int buf, auto set_c) __attribute__((always_inline)) {
+    constexpr int set = decltype(set_c)::value;
+    if (ct + 1 < n_ct) fetch_tile(ct + 1, std::integral_constant<int, (set ^ 1)>());
+    if (256 * (ct + 1) > n) {                                // uniform: this tile reaches past the prompt
+      const u32x4 zero = {0, 0, 0, 0};
+#pragma unroll
+      for (int st = 0; st < ST; ++st) kreg[set][st] = key_of(ct, st) < n ? kreg[set][st] : zero;
+    }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < ST; ++st)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kreg[set][st]), qf[st], acc, 0, 0, 0);
+    // acc[i] = square (a0 + nn, 16*ct + 4g + i): stored as part[a][b]
+    *(f32x4*)(part + ((buf * 4 + w) * 16 + nn) * 16 + 4 * g) = acc;
+  };
+  // the reduction phase: thread (ra, rb) of the workgroup owns square (a0 + ra, 16*ct + rb)
+  const int ra = tid >> 4, rb = tid & 15;
+  const int a_abs = a0 + ra;
+  auto square_value = [&](int ct, int buf) __attribute__((always_inline)) -> float {
+    const int b_abs = 16 * ct + rb;
+    if (a_abs > a_last || b_abs > a_abs) return -INFINITY;               // no such square
+    const int r_min = max(max(b_abs == a_abs ? 8 : 0, kXaStride * b_abs + kXaStride - n), 0);
+    const int r_max = min(kXaStride - 1, n - 1 - kXaStride * a_abs);
+    const int cnt = r_max - r_min + 1;
+    if (cnt <= 0) return -INFINITY;
+    const float* p = part + (buf * 4 * 16 + ra) * 16 + rb;
+    // on the diagonal the samples r < 8 (waves 0 and 1) are not causal
+    const float lo = b_abs == a_abs ? 0.f : p[0] + p[256];
+    const float sum = lo + (p[512] + p[768]);
+    return a.scale * sum / (float)cnt;
+  };
+
+  // ---- first walk: maximum and sum of every row of squares (the 16 lanes rb = 0..15 of a row agree on both)
+  float m_row = -INFINITY, l_row = 0.f;
+  auto first_walk = [&](int ct, auto set_c) __attribute__((always_inline)) {
+    const int buf = ct & 1;
+    partial_tile(ct, buf, set_c);
+    __syncthreads();
+    const float e = square_value(ct, buf);
+    float mt = e;
+    mt = fmaxf(mt, __shfl_xor(mt, 1));
+    mt = fmaxf(mt, __shfl_xor(mt, 2));
+    mt = fmaxf(mt, __shfl_xor(mt, 4));
+    mt = fmaxf(mt, __shfl_xor(mt, 8));
+    const float m_new = fmaxf(m_row, mt);
+    float pe = e == -INFINITY ? 0.f : __expf(e - m_new);
+    pe += __shfl_xor(pe, 1);
+    pe += __shfl_xor(pe, 2);
+    pe += __shfl_xor(pe, 4);
+    pe += __shfl_xor(pe, 8);
+    l_row = (m_row == -INFINITY ? 0.f : l_row * __expf(m_row - m_new)) + pe;
+    m_row = m_new;
+  };
+  fetch_tile(0, std::integral_constant<int, 0>());
+  for (int ct = 0; ct < n_ct; ct += 2) {                    // unrolled by two: the register set is a constant
+    first_walk(ct, std::integral_constant<int, 0>());
+    if (ct + 1 < n_ct) first_walk(ct + 1, std::integral_constant<int, 1>());
+  }
+  // ---- second walk: probabilities, summed 4 x 4 into block masses.  Wave wv of this phase holds the square rows
+  // 4wv .. 4wv+3 (query block 4*grp + wv); a key block is 4 adjacent square columns.
+  const int rows_in_block = min(4, n_sq - (a0 + 4 * w));              // rows of e this wave's query block has
+  auto second_walk = [&](int ct, auto set_c) __attribute__((always_inline)) {
+    const int buf = ct & 1;
+    partial_tile(ct, buf, set_c);
+    __syncthreads();
+    const float e = square_value(ct, buf);
+    float p = (e == -INFINITY || l_row == 0.f) ? 0.f : __expf(e - m_row) / l_row;
+    p += __shfl_xor(p, 1);                                            // over the 4 square columns of a key block
+    p += __shfl_xor(p, 2);
+    p += __shfl_xor(p, 16);                                           // over the 4 square rows of the query block
+    p += __shfl_xor(p, 32);
+    if ((l & 0x33) == 0 && rows_in_block > 0) {
+      const int kbk = 4 * ct + (rb >> 2);
+      if (kbk < a.n_kblocks) mass[w * a.n_kblocks + kbk] = p / (float)rows_in_block;
+    }
+  };
+  __syncthreads();                                                    // the first walk's last readers are done
+  fetch_tile(0, std::integral_constant<int, 0>());
+  for (int ct = 0; ct < n_ct; ct += 2) {
+    second_walk(ct, std::integral_constant<int, 0>());
+    if (ct + 1 < n_ct) second_walk(ct + 1, std::integral_constant<int, 1>());
+  }
+  __syncthreads();
+
+  // ---- selection: wave w owns query block qb_abs = 4*grp + w and its masses of key blocks 0 .. qb_abs
+  const int qb_abs = 4 * grp + w;
+  if (qb_abs >= a.n_qblocks) return;
+  uint8_t* mrow = mrow0 + (int64_t)w * a.n_kblocks;
+  const int n_blk = (n + 63) / 64;
+  if (qb_abs >= n_blk) {                                              // a row of the matrix beyond the prompt
+    for (int j = l; j < a.n_kblocks; j += 64) mrow[j] = 0;
+    return;
+  }
+  const float* mq = mass + w * a.n_kblocks;
+  const int nj = min(qb_abs + 1, a.n_kblocks);
+  auto wave_sum = [&](float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+  };
+  float tot = 0.f, mx = 0.f;
+  for (int j = l; j < nj; j += 64) {
+    tot += mq[j];
+    mx = fmaxf(mx, mq[j]);
+  }
+  tot = wave_sum(tot);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  const float need = a.threshold * tot;
+  // largest t (as a bit pattern; positive floats order like their bits) with sum(mass >= t) >= need
+  uint32_t lo = 0, hi = __builtin_bit_cast(uint32_t, mx) + 1;         // feasible at lo, not at hi (or hi is past the maximum)
+  while (hi - lo > 1) {
+    const uint32_t mid = lo + (hi - lo) / 2;
+    const float t = __builtin_bit_cast(float, mid);
+    float s = 0.f;
+    for (int j = l; j < nj; j += 64) s += mq[j] >= t ? mq[j] : 0.f;
+    s = wave_sum(s);
+    if (s >= need) lo = mid; else hi = mid;
+  }
+  const float cut = __builtin_bit_cast(float, lo);
+  for (int j = l; j < a.n_kblocks; j += 64) mrow[j] = (j < nj && (mq[j] >= cut || j == qb_abs)) ? 1 : 0;
+}
+
+hipError_t launch_xa_select(const Ctx& c, const flux_attn_cfg& cfg, const void* q, const int32_t* cu_q, int max_q_len,
+                            const flux_kv_cache& cache, float threshold, uint8_t* mask, int n_qblocks, int n_kblocks,
+                            hipStream_t s) {
+  XaArgs a;
+  a.q = (const __bf16*)q;
+  a.cu_q = cu_q;
+  a.k = (const __bf16*)cache.k;
+  a.stride_b = cache.stride_b;
+  a.stride_h = cache.stride_h;
+  a.stride_t = cache.stride_t;
+  a.kv_len = cache.kv_len;
+  a.capacity = cache.capacity;
+  a.hq = cfg.n_q_heads;
+  a.group = cfg.n_q_heads / cfg.n_kv_heads;
+  a.scale = cfg.softmax_scale != 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.head_dim);
+  a.threshold = threshold;
+  a.mask = mask;
+  a.n_qblocks = n_qblocks;
+  a.n_kblocks = n_kblocks;
+  a.status = c.status;
+  const int groups = (n_qblocks + 3) / 4;                 // every row of the matrix is written
+  (void)max_q_len;
+  const dim3 grid(groups, cfg.n_q_heads, cache.batch);
+  const size_t lds = xa_select_lds_bytes(n_kblocks);
+  if (cfg.head_dim == 128) {
+    if (lds > 48 * 1024) {
+      const hipError_t e = hipFuncSetAttribute((const void*)xa_select_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(xa_select_kernel<128>, grid, dim3(256), lds, s, a);
+  } else {
+    if (lds > 48 * 1024) {
+      const hipError_t e = hipFuncSetAttribute((const void*)xa_select_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(xa_select_kernel<64>, grid, dim3(256), lds, s, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace flux

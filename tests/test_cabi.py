@@ -191,3 +191,18 @@ def test_blocksparse_argument_validation(F, nodev):
     assert call(mk=64, nk=1) == F.FLUX_EHIP
     assert call(mk=65, nk=1) == F.FLUX_ECAPACITY                   # beyond the cache capacity of the fixture
     assert call(cfg=F.attn_cfg(8, 3, 128, 0, 1)) == F.FLUX_EINVAL
+
+
+def test_xa_select_argument_validation(F, nodev):
+    good = F.attn_cfg(8, 2, 128, 0, 1)
+    kc = cache_struct(F)
+    call = lambda **kw: rc_of(F, F.flux_xa_select, nodev, kw.get("cfg", good), 4096, 768, 64, 64, kc, kw.get("stride", 16),
+                              kw.get("thr", 0.9), kw.get("mask", 2048), kw.get("nq", 1), kw.get("nk", 1))
+    assert call() == F.FLUX_EHIP
+    assert call(stride=8) == F.FLUX_EINVAL                          # the stride of Table 3 is the one built
+    assert call(thr=0.0) == F.FLUX_EINVAL and call(thr=1.5) == F.FLUX_EINVAL and call(thr=float("nan")) == F.FLUX_EINVAL
+    assert call(thr=1.0) == F.FLUX_EHIP
+    assert call(mask=None) == F.FLUX_EINVAL
+    assert call(nq=0) == F.FLUX_EINVAL and call(nk=0) == F.FLUX_EINVAL
+    assert call(nk=4097) == F.FLUX_EINVAL                           # more key blocks than the kernel's LDS holds
+    assert call(cfg=F.attn_cfg(8, 2, 96, 0, 1)) == F.FLUX_EINVAL

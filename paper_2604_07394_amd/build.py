@@ -35,6 +35,25 @@ def build_all(verbose: bool = False) -> None:
                          os.path.join(LIB, "libflux_synth.so")])
     if verbose and out:
         print(out)
+    build_hostcheck(verbose)
+
+
+# The C ABI's host side (argument validation, workspace arithmetic, the sink / window rounding) built once more as
+# plain C++ under AddressSanitizer and UndefinedBehaviorSanitizer, with launchers that report "no device", and a
+# small driver that calls every entry point with ordinary and extreme arguments.  No GPU is needed to run it.
+SAN = ["-O1", "-g", "-std=c++17", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=all"]
+CLANGXX = "/opt/rocm/lib/llvm/bin/clang++"
+
+
+def build_hostcheck(verbose: bool = False) -> None:
+    inc = ["-I/opt/rocm/include", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+    out = _run([CLANGXX, "-x", "c++", "-D__HIP_PLATFORM_AMD__"] + inc + SAN + ["-fPIC", "-shared",
+               os.path.join(CSRC, "flux_api.hip"), os.path.join(CSRC, "hostcheck_stubs.cpp"), "-L/opt/rocm/lib", "-lamdhip64",
+               "-Wl,-rpath,/opt/rocm/lib", "-o", os.path.join(LIB, "libflux_hostcheck.so")])
+    out += _run([CLANGXX] + SAN + [os.path.join(CSRC, "hostcheck_main.cpp"), "-L" + LIB, "-lflux_hostcheck",
+                "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib", "-o", os.path.join(LIB, "flux_hostcheck")])
+    if verbose and out:
+        print(out)
 
 
 if __name__ == "__main__":

@@ -67,10 +67,7 @@ __device__ __forceinline__ int visible_len(int n, int md, int sink_lim, int win_
   return sparse ? s_end + (n - tail_start) : n;
 }
 
-constexpr int kTargetShift = 10;                // about 1024 workgroups: 4 per CU, two rounds of the two that fit a CU
-constexpr int kTargetUnits = 1 << kTargetShift;
 constexpr int kResidentUnits = 512;             // workgroups the chip holds at once (two per CU at this register count)
-constexpr int kMinChunk = 256;                  // 64 keys per wave: keeps the per-chunk merge a small part of the streaming
 
 // Length and mode of sequence b under the clamp: a length the host could not see (negative, or past the
 // capacity of a full cache) is cut and reported through `bad`.
@@ -468,24 +465,6 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
   const int64_t off = ((int64_t)b * a.hq + head) * D + d;
   if (a.out_fp32) ((float*)a.out)[off] = r;
   else ((__bf16*)a.out)[off] = (__bf16)r;
-}
-
-DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len) {
-  // Upper bound on the units the device-side split can produce: kTargetUnits + one per pair from the chunk
-  // size it picks, and no more than the pairs times the chunks of the longest list at the smallest chunk.
-  DecodePlan p;
-  const int group = cfg.n_q_heads / cfg.n_kv_heads;
-  p.pps = cfg.n_kv_heads * ((group + 15) / 16);
-  p.rpu = group < 16 ? group : 16;
-  const long long pairs = (long long)batch * p.pps;
-  const long long by_len = pairs * (((long long)(max_kv_len > 0 ? max_kv_len : 1) + kMinChunk - 1) / kMinChunk);
-  const long long by_target = kTargetUnits + pairs;
-  p.units = (int)(by_len < by_target ? by_len : by_target);
-  return p;
-}
-
-size_t decode_partials_bytes(const flux_attn_cfg& cfg, const DecodePlan& p) {
-  return (size_t)p.units * p.rpu * (cfg.head_dim + 2) * sizeof(float);
 }
 
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,

@@ -6,6 +6,20 @@
 
 #include "../../include/flux.h"
 
+// The host-only build that checks the C ABI under sanitizers compiles flux_api.hip as plain C++ (no device pass):
+// there the few device-side spellings it meets are given host meanings.
+#ifndef __HIP__
+#ifndef __device__
+#define __device__
+#endif
+#ifndef __align__
+#define __align__(n) __attribute__((aligned(n)))
+#endif
+#ifndef HIP_SYMBOL
+#define HIP_SYMBOL(x) x
+#endif
+#endif
+
 namespace flux {
 
 // ---- vector types for MFMA operands and packed memory access --------------------------------
@@ -53,10 +67,12 @@ inline SaGeom sa_geom(const flux_attn_cfg& cfg) {
   g.win_blocks = win_blocks > (0x7FFFFFFFll >> sh) ? (0x7FFFFFFF >> sh) : (int)win_blocks;
   return g;
 }
+#ifdef __HIP__   // device helpers: absent from the host-only build that checks the C ABI under sanitizers
 __device__ __forceinline__ int window_start(int i, int shift, int win_blocks) {
   const int lo = ((i >> shift) - win_blocks + 1) << shift;
   return lo > 0 ? lo : 0;
 }
+#endif
 
 constexpr int kCounters = 64;
 constexpr size_t kSmallBytes = 8u << 20;      // router: batch * (splits * hidden + inner) floats
@@ -74,8 +90,27 @@ struct DecodePlan {
   int pps;          // (KV head, query block) pairs per sequence
   int rpu;          // partial rows each unit writes
 };
-DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len);
-size_t decode_partials_bytes(const flux_attn_cfg& cfg, const DecodePlan& p);
+// The split-K decode cuts the visible keys of a call into about kTargetUnits workgroups of at least kMinChunk keys
+// (the split itself is taken on the device; the host only bounds it).
+constexpr int kTargetShift = 10;                // about 1024 workgroups: 4 per CU, two rounds of the two that fit a CU
+constexpr int kTargetUnits = 1 << kTargetShift;
+constexpr int kMinChunk = 256;                  // 64 keys per wave: keeps the per-chunk merge a small part of the streaming
+inline DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len) {
+  // Upper bound on the units the device-side split can produce: kTargetUnits + one per pair from the chunk
+  // size it picks, and no more than the pairs times the chunks of the longest list at the smallest chunk.
+  DecodePlan p;
+  const int group = cfg.n_q_heads / cfg.n_kv_heads;
+  p.pps = cfg.n_kv_heads * ((group + 15) / 16);
+  p.rpu = group < 16 ? group : 16;
+  const long long pairs = (long long)batch * p.pps;
+  const long long by_len = pairs * (((long long)(max_kv_len > 0 ? max_kv_len : 1) + kMinChunk - 1) / kMinChunk);
+  const long long by_target = kTargetUnits + pairs;
+  p.units = (int)(by_len < by_target ? by_len : by_target);
+  return p;
+}
+inline size_t decode_partials_bytes(const flux_attn_cfg& cfg, const DecodePlan& p) {
+  return (size_t)p.units * p.rpu * (cfg.head_dim + 2) * sizeof(float);
+}
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
                          const flux_kv_cache& cache, const uint8_t* mode, int ring, void* out, hipStream_t s);
 
@@ -100,6 +135,7 @@ hipError_t launch_router(const Ctx& c, const void* x, const int32_t* cu_seqlens,
                          uint8_t* mode_out, float* logits_out, hipStream_t s);
 
 // ---- small device helpers -------------------------------------------------------------------
+#ifdef __HIP__
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
   return __builtin_bit_cast(float, bits16 << 16);
 }
@@ -127,5 +163,6 @@ __device__ __forceinline__ float sum_across_halves(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
 }
+#endif  // __HIP__
 
 }  // namespace flux

@@ -561,7 +561,12 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           for (int i = 0; i < 4; ++i) s[kb][qb][i] = 16 * kb + i <= hi ? s[kb][qb][i] : -INFINITY;
       }
     }
+    // The softmax part runs at a raised wave priority: while it is short, the other wave of this SIMD is mostly
+    // inside a run of MFMAs, which queue on the matrix pipe anyway, so letting the vector work through first
+    // shortens this wave's way back to its own MFMAs (measured: +2.7 % on the FA launch).
+    __builtin_amdgcn_s_setprio(1);
     weights_guarded();
+    __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     load_v(1);
     __builtin_amdgcn_sched_barrier(0);

@@ -296,28 +296,36 @@ def main():
         torch.cuda.synchronize()
         cur = {"n": N}
 
-        def decode_step(mask, events=None):
+        def decode_step(mask, events=None, fused=True):
+            """One decode step of the stack: per layer, append the new K/V row of every sequence and attend.
+            fused: one flux_attn_decode_append call per layer (two launches); else flux_kv_append followed by
+            flux_attn_decode (three launches, the same results bit for bit)."""
             cur["n"] += 1
             for l in range(LD):
-                F.flux_kv_append(ctx, dcaches[l], HKV, D, kd[0, l], vd[0, l], cu1, B, 1)
+                if not fused:
+                    F.flux_kv_append(ctx, dcaches[l], HKV, D, kd[0, l], vd[0, l], cu1, B, 1)
                 if events is not None:
                     e0 = torch.cuda.Event(enable_timing=True)
                     e1 = torch.cuda.Event(enable_timing=True)
                     e0.record()
                 # the cached mask is known on the host after prefill: SA layers are sized for sinks + window
                 bound = cur["n"] if mask[l] else min(cur["n"], NS + W)
-                F.flux_attn_decode(ctx, cfg, qd[0, l], bound, dcaches[l], dmodes[int(mask[l])], outd)
+                if fused:
+                    F.flux_attn_decode_append(ctx, cfg, qd[0, l], kd[0, l], vd[0, l], bound, dcaches[l],
+                                              dmodes[int(mask[l])], outd)
+                else:
+                    F.flux_attn_decode(ctx, cfg, qd[0, l], bound, dcaches[l], dmodes[int(mask[l])], outd)
                 if events is not None:
                     e1.record()
                     events.append((int(mask[l]), e0, e1))
 
-        def time_decode(mask, steps, warmup, events=None):
+        def time_decode(mask, steps, warmup, events=None, fused=True):
             for _ in range(warmup):
-                decode_step(mask)
+                decode_step(mask, fused=fused)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(steps):
-                decode_step(mask, events)
+                decode_step(mask, events, fused)
             torch.cuda.synchronize()
             return (time.perf_counter() - t0) / steps
 
@@ -329,6 +337,9 @@ def main():
         kv_len.fill_(N)
         cur["n"] = N
         td_fa = time_decode(np.ones(LD, dtype=np.uint8), half, 2) if args.mask == "mix" else None
+        kv_len.fill_(N)
+        cur["n"] = N
+        td_mix_3 = time_decode(mask_d, half, 2, fused=False) if args.mask == "mix" else None
         # ---- sparse-decode residency (Sec. 3.3): the SA layers keep only sinks + window rows in a ring cache,
         # compacted from the full cache as after a prefill; FA layers keep the full cache
         ring_info = None
@@ -375,8 +386,8 @@ def main():
 
             def graph_step():
                 for l in range(LD):
-                    F.flux_kv_append(ctx, dcaches[l], HKV, D, kd[0, l], vd[0, l], cu1, B, 1)
-                    F.flux_attn_decode(ctx, cfg, qd[0, l], cap if mask_d[l] else NS + W, dcaches[l], dmodes[int(mask_d[l])], outd)
+                    F.flux_attn_decode_append(ctx, cfg, qd[0, l], kd[0, l], vd[0, l], cap if mask_d[l] else NS + W,
+                                              dcaches[l], dmodes[int(mask_d[l])], outd)
 
             graph_step()
             torch.cuda.synchronize()
@@ -404,11 +415,13 @@ def main():
                         "%d of %d layers SA (%d sinks + %d window), seed %d" % (LD, B, N, HQ, HKV, D, LD - n_fa, LD, NS, W, SEED_D),
             "ms_per_step_mix": td_mix * 1e3, "ms_per_step_all_fa": td_fa * 1e3 if td_fa else None,
             "speedup_mix_vs_all_fa": td_fa / td_mix if td_fa else None,
+            "layer_call": "flux_attn_decode_append (the new row of every sequence is appended inside the decode call)",
+            "ms_per_step_mix_append_then_decode": td_mix_3 * 1e3 if td_mix_3 else None,
             "predicted_speedup_from_bytes": (LD * bytes_fa) / (n_fa * bytes_fa + (LD - n_fa) * bytes_sa),
             "fa_layer_ms": fa_avg, "sa_layer_ms": sa_avg,
             "fa_layer_ms_median": float(np.median(fa_ms)) if fa_ms else None,
             "sa_layer_ms_median": float(np.median(sa_ms)) if sa_ms else None,
-            "roofline": {"kernel": "decode_splitk_kernel<128, true> + decode_combine_kernel<128> (FA layers)",
+            "roofline": {"kernel": "decode_splitk_kernel<128, true, true> + decode_combine_kernel<128> (FA layers)",
                          "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": ach / PEAK_HBM_GBS,
                          "traffic": None, "traffic_note": "not the profiled workload",

@@ -193,6 +193,21 @@ int flux_xa_select(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const
 int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int max_kv_len,
                      const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream);
 
+/* One whole decode step of a layer (Sec. 3.3, the decode path; App. B.3): the same result and the same cache
+ * contents as flux_kv_append of one row per sequence followed by flux_attn_decode, bit for bit, in two launches
+ * instead of three (for a sparse layer, whose kernels run for some tens of microseconds, the append launch is a
+ * tenth of the step).
+ *   k_new, v_new: dev bf16 [batch, n_kv_heads, head_dim], 16-byte aligned: the row sequence b appends at position
+ *                 kv_len[b] (before the call).  A sequence whose cache is full drops its row, raises
+ *                 FLUX_DEV_KV_OVERFLOW and attends to what is cached, as the pair of calls would.
+ *   max_kv_len:   >= 1; bound on the keys any sequence attends to AFTER the append (see flux_attn_decode).
+ *   cache:        a full cache (not a ring); kv_len[b] is read by every workgroup and moved on at the end of the
+ *                 call (kv_len[b] += 1, cut at the capacity).
+ * Other arguments as flux_attn_decode.  The workgroup that owns the end of a sequence's key list stores the new row;
+ * workgroups that attend to it read it from k_new / v_new; the merge kernel moves the lengths on. */
+int flux_attn_decode_append(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const void* k_new, const void* v_new,
+                            int max_kv_len, const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream);
+
 /* flux_attn_decode for callers that cannot allocate device memory at all (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): no context, and no hipMalloc / hipFree / allocating library
  * call inside.  The split-K partial results go to a static device array of FLUX_STATIC_SCRATCH_BYTES that

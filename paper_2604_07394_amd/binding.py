@@ -27,7 +27,7 @@ FA, SA = 1, 0
 EXPORTS = ["flux_create", "flux_destroy", "flux_strerror", "flux_workspace_needed", "flux_last_device_status",
            "flux_router", "flux_kv_append", "flux_attn_prefill", "flux_attn_decode",
            "flux_kv_append_ring", "flux_kv_compact_ring", "flux_attn_decode_ring", "flux_attn_decode_static",
-           "flux_attn_prefill_blocksparse", "flux_xa_select"]
+           "flux_attn_prefill_blocksparse", "flux_xa_select", "flux_attn_decode_append"]
 STATIC_SCRATCH_BYTES = 16 * 1024 * 1024 + 256
 
 
@@ -72,6 +72,9 @@ _lib.flux_xa_select.restype = C.c_int
 _lib.flux_attn_decode.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_int, C.POINTER(FluxKVCache),
                                   C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.flux_attn_decode.restype = C.c_int
+_lib.flux_attn_decode_append.argtypes = [C.c_void_p, C.POINTER(FluxAttnCfg), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                         C.POINTER(FluxKVCache), C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.flux_attn_decode_append.restype = C.c_int
 _lib.flux_attn_decode_static.argtypes = [C.POINTER(FluxAttnCfg), C.c_void_p, C.c_int, C.POINTER(FluxKVCache), C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.flux_attn_decode_static.restype = C.c_int
@@ -205,6 +208,12 @@ def flux_attn_decode(ctx, cfg, q, max_kv_len, cache, mode, out, stream=None) -> 
     cs = _cache_struct(cache)
     _check(_lib.flux_attn_decode(ctx, C.byref(cfg), _ptr(q), max_kv_len, C.byref(cs), _ptr(mode), _ptr(out),
                                  _stream(stream)))
+
+
+def flux_attn_decode_append(ctx, cfg, q, k_new, v_new, max_kv_len, cache, mode, out, stream=None) -> None:
+    cs = _cache_struct(cache)
+    _check(_lib.flux_attn_decode_append(ctx, C.byref(cfg), _ptr(q), _ptr(k_new), _ptr(v_new), max_kv_len, C.byref(cs),
+                                        _ptr(mode), _ptr(out), _stream(stream)))
 
 
 def flux_attn_decode_static(cfg, q, max_kv_len, cache, mode, out, status=None, stream=None) -> None:

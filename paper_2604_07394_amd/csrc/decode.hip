@@ -40,6 +40,7 @@ struct SplitArgs {
   int sink_lim, win_blocks, blk_shift;   // SA geometry (see sa_geom)
   int max_keys;           // the host's bound on the keys any sequence attends to
   int pps;                // (KV head, query block) pairs per sequence = hkv * qblocks
+  int bump;               // 1: the call also appends one row per sequence, so every list is one key longer than kv_len says
 };
 
 struct DecodeArgs {
@@ -53,7 +54,11 @@ struct DecodeArgs {
   int rpu;                // partial rows per unit = min(group, 16)
   float scale_log2;       // softmax scale * log2(e)
   float* partials;        // per pair [rpu, chunks of the pair, D + 2], pairs in unit order
+  int* table;             // [batch][2]: first unit and chunks per pair of every sequence, for the merge kernel
   uint32_t* status;       // sticky device status word
+  // the fused decode step only: the row each sequence appends at position kv_len[b], [B, Hkv, D]
+  const __bf16* k_new;
+  const __bf16* v_new;
 };
 
 // Number of keys the query at position n - 1 attends to.  The visible list is the sinks [0, s_end)
@@ -63,19 +68,26 @@ __device__ __forceinline__ int visible_len(int n, int md, int sink_lim, int win_
   s_end = n < sink_lim ? n : sink_lim;
   const int lo = n > 0 ? window_start(n - 1, shift, win_blocks) : 0;
   tail_start = lo > s_end ? lo : s_end;
-  sparse = (md == 0) && (tail_start > s_end);
+  sparse = ((md & 1) == 0) && (tail_start > s_end);          // bit 0 of md: 1 = FA
   return sparse ? s_end + (n - tail_start) : n;
 }
 
-constexpr int kResidentUnits = 512;             // workgroups the chip holds at once (two per CU at this register count)
+constexpr int kResidentUnits = 768;             // workgroups the chip holds at once (three per CU at this register count)
 
 // Length and mode of sequence b under the clamp: a length the host could not see (negative, or past the
 // capacity of a full cache) is cut and reported through `bad`.
+// With s.bump the length returned counts the row the call appends, and bit 1 of md says that it does (a full cache
+// drops the row).
 __device__ __forceinline__ void load_seq(const SplitArgs& s, int b, int& len, int& md, bool& bad) {
   len = s.kv_len[b];
   md = s.ring ? 0 : s.mode[b];
   bad = len < 0 || (!s.ring && len > s.capacity);
   len = len < 0 ? 0 : ((!s.ring && len > s.capacity) ? s.capacity : len);
+  md = md != 0 ? 1 : 0;
+  if (s.bump && len < s.capacity) {
+    ++len;
+    md |= 2;
+  }
 }
 
 // Visible keys of a sequence of `len` rows in mode `md`, cut at the host's bound (reported through `bad`).
@@ -183,7 +195,72 @@ __device__ __forceinline__ Split find_split(const SplitArgs& s, int lane, int un
   return r;
 }
 
-template <int D, bool NT>
+// Merge the chunks of one (sequence, query head): out[d] = sum_c w_c O_c[d] / sum_c w_c l_c, w_c = exp(m_c - max m),
+// chunks taken in index order.  Called by D consecutive threads (d = 0 .. D-1, whole waves) that share `wgt` (D floats)
+// and `red` (4 floats) in LDS.  It holds workgroup barriers: every thread of the workgroup makes the call, each group
+// of D threads with its own arrays and the same nc.  base: the head's rows [chunk][D + 2] of the workspace.
+// The split as a table, for the merge kernel: entry b = (first unit, chunks per pair) of sequence b.  One wave writes
+// it (lane i looks after sequences i, i + 64, ...), with the same arithmetic as find_split.
+__device__ __forceinline__ void write_split_table(const SplitArgs& s, int lane, int chunk, int* table) {
+  bool sparse, bad;
+  int s_end, tail_start;
+  for (int b0 = 0, base = 0; b0 < s.batch; b0 += 64) {
+    int len = 0, md = 1, nv = 0;
+    if (b0 + lane < s.batch) {
+      load_seq(s, b0 + lane, len, md, bad);
+      nv = seq_visible(s, len, md, bad, sparse, s_end, tail_start);
+    }
+    const int nc = (nv + chunk - 1) / chunk;
+    const int incl = wave_inclusive_sum(s.pps * nc);
+    if (b0 + lane < s.batch) {
+      table[2 * (b0 + lane)] = base + incl - s.pps * nc;
+      table[2 * (b0 + lane) + 1] = nc;
+    }
+    base += __builtin_amdgcn_readlane(incl, 63);
+  }
+}
+
+template <int D>
+__device__ __forceinline__ float merge_head(const float* base, int nc, float scale_log2, int d, float* wgt, float* red) {
+  constexpr int RED = D + 2;
+  // ---- maximum over the chunks (threads take chunks round-robin, then a reduction over the group's waves)
+  float m = -INFINITY;
+  for (int c = d; c < nc; c += D) m = fmaxf(m, base[c * RED + D]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if ((d & 63) == 0) red[d >> 6] = m;
+  __syncthreads();
+  m = D == 128 ? fmaxf(red[0], red[1]) : red[0];
+  // ---- weights per chunk in LDS, D chunks at a time; every thread then sums its own column
+  float num = 0.f, den = 0.f;
+  for (int c0 = 0; c0 < nc; c0 += D) {
+    __syncthreads();
+    const int c = c0 + d;
+    float w = 0.f, l = 0.f;
+    if (c < nc) {
+      w = fast_exp2((base[c * RED + D] - m) * scale_log2);
+      l = base[c * RED + D + 1];
+    }
+    wgt[d] = w;
+    den += w * l;                                            // partial; reduced over the group below
+    __syncthreads();
+    const int cn = min(D, nc - c0);
+    for (int cc = 0; cc < cn; ++cc) num += wgt[cc] * base[(c0 + cc) * RED + d];
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off);
+  __syncthreads();
+  if ((d & 63) == 0) red[2 + (d >> 6)] = den;
+  __syncthreads();
+  den = D == 128 ? red[2] + red[3] : red[2];
+  return nc > 0 ? num / den : 0.f;                          // an empty cache yields zeros
+}
+
+// FUSED: the call is a whole decode step of the layer (Sec. 3.3): it also appends the row k_new / v_new of every
+// sequence at position kv_len[b].  The unit that owns the end of a list stores the row in the cache; the units that
+// attend to it take it from k_new / v_new, so no read waits for that store.  The lengths are moved on by the merge
+// kernel, after every workgroup of both kernels has read them.  Two launches instead of three.
+template <int D, bool NT, bool FUSED>
 __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   constexpr int KC = D / 32;          // MFMA k-steps over the head dimension
   constexpr int DB = D / 16;          // 16-wide output blocks over the head dimension
@@ -202,6 +279,9 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   // ---- the split: chunk size from the whole batch, then the sequence whose units contain `unit`
   const Split sp = find_split(a.sp, l, unit, -1);
   if (unit == 0 && w == 0 && sp.any_bad) atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
+  // the last workgroup of the grid (idle unless the host's bound on the units is met exactly) leaves the split
+  // behind for the merge kernel, which then needs neither the lengths nor the scan
+  if (unit == (int)gridDim.x - 1 && w == 0) write_split_table(a.sp, l, sp.chunk, a.table);
   if (sp.b < 0) return;                                     // past the last unit: uniform for the whole workgroup
   const int b = sp.b, chunk = sp.chunk;
   const int local = unit - sp.first_unit;                   // < pps * nc, chunk index fastest
@@ -223,6 +303,26 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
 
   const __bf16* kbase = a.k + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
   const __bf16* vbase = a.v + (int64_t)b * a.stride_b + (int64_t)kvh * a.stride_h;
+
+  // FUSED: the appended row is position sp.len - 1, the last key of every list (none when the cache was full).
+  int new_key = -1;
+  const __bf16* knew = nullptr;
+  const __bf16* vnew = nullptr;
+  if constexpr (FUSED) {
+    if (sp.md & 2) {                                         // the sequence takes its row
+      new_key = sp.len - 1;
+      knew = a.k_new + ((int64_t)b * a.hkv + kvh) * D;
+      vnew = a.v_new + ((int64_t)b * a.hkv + kvh) * D;
+      if (ci == sp.nc - 1 && qb == 0 && tid < 2 * CPR) {     // this unit owns the end of the list: it stores the row
+        const int c = tid % CPR;
+        const __bf16* src = (tid < CPR ? knew : vnew) + 8 * c;
+        __bf16* dst = const_cast<__bf16*>(tid < CPR ? kbase : vbase) + (int64_t)new_key * a.stride_t + 8 * c;
+        *(u32x4*)dst = *(const u32x4*)src;
+      }
+    } else if (ci == 0 && pair == 0 && tid == 0) {
+      atomicOr(a.status, (uint32_t)FLUX_DEV_KV_OVERFLOW);
+    }
+  }
 
   // ---- Q operand: lane (n, g) holds d = 32*kc + 8*g .. +7 of query head kvh*group + 16*qb + n
   const int qh = 16 * qb + n;
@@ -248,11 +348,11 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   // A 32-key block whose keys are 32 consecutive cache rows (every block of an FA chunk, and all but the
   // few SA blocks that contain the sink / tail seam, the ring wrap or the end of the list) is addressed as
   // a wave-uniform row pointer plus per-lane offsets fixed for the whole kernel: no per-lane multiplies.
-  int k_lane[2], v_lane[VL];                                // element offsets inside a block of consecutive rows
-#pragma unroll
-  for (int sb = 0; sb < 2; ++sb) k_lane[sb] = (16 * sb + n) * (int)a.stride_t + 8 * g;
-#pragma unroll
-  for (int i = 0; i < VL; ++i) v_lane[i] = ((i * 64 + l) / CPR) * (int)a.stride_t + ((i * 64 + l) % CPR) * 8;
+  // The lane's offset is the same for every load of a block (one register for K, one for V); what differs between
+  // the loads, 16 rows per K half and 64 / CPR rows per V load, is added to the uniform row pointer.
+  constexpr int RPL = 64 / CPR;                             // V rows per wave-wide load
+  const int k_lane = n * (int)a.stride_t + 8 * g;           // element offsets inside a block of consecutive rows
+  const int v_lane = (l / CPR) * (int)a.stride_t + (l % CPR) * 8;
 
   // When the rows of one call exceed the last-level cache they are read once and evicted before the next
   // step: NT selects nontemporal loads, which measurably raise the streaming rate of this access shape
@@ -261,27 +361,30 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   u32x4 kreg[2][KC], vreg[VL];
   auto load_block = [&](int p0) {                           // p0 is wave-uniform
     const int64_t r0 = key_of(p0);
-    const bool linear = p0 + 32 <= c1 && key_of(p0 + 31) - r0 == 31;
+    // (FUSED: the block that holds the appended row takes the per-lane path, where that row comes from k_new / v_new)
+    const bool linear = p0 + 32 <= c1 && key_of(p0 + 31) - r0 == 31 && !(FUSED && new_key >= 0 && r0 + 31 >= new_key);
     if (linear) {
       const __bf16* kb0 = kbase + r0 * a.stride_t;
       const __bf16* vb0 = vbase + r0 * a.stride_t;
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = ld((const u32x4*)(kb0 + k_lane[sb] + 32 * kc));
+        for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = ld((const u32x4*)(kb0 + 16 * sb * a.stride_t + k_lane + 32 * kc));
 #pragma unroll
-      for (int i = 0; i < VL; ++i) vreg[i] = ld((const u32x4*)(vb0 + v_lane[i]));
+      for (int i = 0; i < VL; ++i) vreg[i] = ld((const u32x4*)(vb0 + i * RPL * a.stride_t + v_lane));
     } else {
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
-        const __bf16* row = kbase + key_of(p0 + 16 * sb + n) * a.stride_t;
+        const int64_t key = key_of(p0 + 16 * sb + n);
+        const __bf16* row = (FUSED && key == new_key) ? knew : kbase + key * a.stride_t;
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) kreg[sb][kc] = ld((const u32x4*)(row + 32 * kc + 8 * g));
       }
 #pragma unroll
       for (int i = 0; i < VL; ++i) {
         const int e = i * 64 + l;
-        const __bf16* row = vbase + key_of(p0 + e / CPR) * a.stride_t;
+        const int64_t key = key_of(p0 + e / CPR);
+        const __bf16* row = (FUSED && key == new_key) ? vnew : vbase + key * a.stride_t;
         vreg[i] = ld((const u32x4*)(row + (e % CPR) * 8));
       }
     }
@@ -309,8 +412,6 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) kf[sb][kc] = __builtin_bit_cast(bf16x8, kreg[sb][kc]);
     const int pnext = p0 + 128;
-    if (pnext < c1) load_block(pnext);                      // prefetch while computing
-
     // ---- scores: s[sb][i] is key p0 + 16*sb + 4*g + i against query n
     f32x4 s[2];
 #pragma unroll
@@ -320,6 +421,11 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
       for (int kc = 0; kc < KC; ++kc)
         s[sb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[sb][kc], qf[kc], s[sb], 0, 0, 0);
     }
+    // the next block is asked for once the score MFMAs have taken this block's K registers, which the loads then
+    // reuse (asked for before them, the block in flight needs registers of its own: 30 more per lane)
+    __builtin_amdgcn_sched_barrier(0);
+    if (pnext < c1) load_block(pnext);
+    __builtin_amdgcn_sched_barrier(0);
     if (p0 + 32 > c1) {
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
@@ -412,10 +518,14 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
 // w_c = exp(m_c - max m), chunks taken in index order.
 struct CombineArgs {
   const float* partials;
-  SplitArgs sp;
+  const int* table;       // the split the first kernel took: [batch][2] = first unit, chunks per pair
   int hq, group, qblocks, rpu, out_fp32;
   float scale_log2;
   void* out;
+  // the fused decode step only (bump = 1): the lengths, which this kernel moves on.  Nothing reads them any more
+  // at that point: the first kernel has ended and this one takes the split from the table.
+  int bump, capacity;
+  int32_t* kv_len_rw;
 };
 
 template <int D>
@@ -424,51 +534,25 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(CombineArgs a) {
   __shared__ float wgt[D];
   __shared__ float red[4];
   const int d = threadIdx.x, head = blockIdx.x, b = blockIdx.y;
-  const int lane = d & 63;
-  // ---- the same split the first kernel took
-  const Split sp = find_split(a.sp, lane, -1, b);
-  const int nc = sp.nc, first_unit = sp.first_unit;
+  const int first_unit = a.table[2 * b], nc = a.table[2 * b + 1];
   const int hh = head % a.group;
   const int64_t unit0 = first_unit + (int64_t)((head / a.group) * a.qblocks + hh / 16) * nc;
   const float* base = a.partials + (unit0 * a.rpu + (int64_t)(hh % 16) * nc) * RED;
-  // ---- maximum over the chunks (threads take chunks round-robin, then a block reduction)
-  float m = -INFINITY;
-  for (int c = d; c < nc; c += D) m = fmaxf(m, base[c * RED + D]);
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-  if ((d & 63) == 0) red[d >> 6] = m;
-  __syncthreads();
-  m = D == 128 ? fmaxf(red[0], red[1]) : red[0];
-  // ---- weights per chunk in LDS, D chunks at a time; every thread then sums its own column
-  float num = 0.f, den = 0.f;
-  for (int c0 = 0; c0 < nc; c0 += D) {
-    __syncthreads();
-    const int c = c0 + d;
-    float w = 0.f, l = 0.f;
-    if (c < nc) {
-      w = fast_exp2((base[c * RED + D] - m) * a.scale_log2);
-      l = base[c * RED + D + 1];
-    }
-    wgt[d] = w;
-    den += w * l;                                            // partial; reduced over the block below
-    __syncthreads();
-    const int cn = min(D, nc - c0);
-    for (int cc = 0; cc < cn; ++cc) num += wgt[cc] * base[(c0 + cc) * RED + d];
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off);
-  __syncthreads();
-  if ((d & 63) == 0) red[2 + (d >> 6)] = den;
-  __syncthreads();
-  den = D == 128 ? red[2] + red[3] : red[2];
-  const float r = nc > 0 ? num / den : 0.f;                 // an empty cache yields zeros
+  const float r = merge_head<D>(base, nc, a.scale_log2, d, wgt, red);
   const int64_t off = ((int64_t)b * a.hq + head) * D + d;
   if (a.out_fp32) ((float*)a.out)[off] = r;
   else ((__bf16*)a.out)[off] = (__bf16)r;
+  if (a.bump && head == 0 && d == 0) {
+    int len = a.kv_len_rw[b];
+    len = len < 0 ? 0 : (len > a.capacity ? a.capacity : len);
+    a.kv_len_rw[b] = len < a.capacity ? len + 1 : len;
+  }
 }
 
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
-                         const flux_kv_cache& cache, const uint8_t* mode, int ring, void* out, hipStream_t s) {
+                         const flux_kv_cache& cache, const uint8_t* mode, int ring, const void* k_new,
+                         const void* v_new, void* out, hipStream_t s) {
+  const bool fused = k_new != nullptr;                       // append + attend + merge in one launch
   const DecodePlan plan = plan_decode(cfg, cache.batch, max_kv_len);
   const float scale = cfg.softmax_scale != 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.head_dim);
   DecodeArgs a;
@@ -489,30 +573,42 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   a.sp.blk_shift = geom.shift;
   a.sp.max_keys = max_kv_len;
   a.sp.pps = plan.pps;
+  a.sp.bump = fused ? 1 : 0;
+  a.k_new = (const __bf16*)k_new;
+  a.v_new = (const __bf16*)v_new;
   a.hq = cfg.n_q_heads;
   a.hkv = cfg.n_kv_heads;
   a.group = cfg.n_q_heads / cfg.n_kv_heads;
   a.qblocks = (a.group + 15) / 16;
   a.rpu = plan.rpu;
   a.scale_log2 = scale * kLog2e;
-  a.partials = c.partials;
+  a.table = (int*)c.partials;                                // the split table sits in front of the partial rows
+  a.partials = c.partials + plan.table_floats;
   a.status = c.status;
   const dim3 grid(plan.units);
   // K and V bytes one call may read, against the 256 MB last-level cache
   const bool nt = 4.0 * cache.batch * cfg.n_kv_heads * cfg.head_dim * (double)max_kv_len > 256.0 * 1024 * 1024;
-  if (cfg.head_dim == 128) {
-    if (nt) hipLaunchKernelGGL((decode_splitk_kernel<128, true>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((decode_splitk_kernel<128, false>), grid, dim3(256), 0, s, a);
+  if (fused) {
+    if (cfg.head_dim == 128) {
+      if (nt) hipLaunchKernelGGL((decode_splitk_kernel<128, true, true>), grid, dim3(256), 0, s, a);
+      else hipLaunchKernelGGL((decode_splitk_kernel<128, false, true>), grid, dim3(256), 0, s, a);
+    } else {
+      if (nt) hipLaunchKernelGGL((decode_splitk_kernel<64, true, true>), grid, dim3(256), 0, s, a);
+      else hipLaunchKernelGGL((decode_splitk_kernel<64, false, true>), grid, dim3(256), 0, s, a);
+    }
+  } else if (cfg.head_dim == 128) {
+    if (nt) hipLaunchKernelGGL((decode_splitk_kernel<128, true, false>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((decode_splitk_kernel<128, false, false>), grid, dim3(256), 0, s, a);
   } else {
-    if (nt) hipLaunchKernelGGL((decode_splitk_kernel<64, true>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((decode_splitk_kernel<64, false>), grid, dim3(256), 0, s, a);
+    if (nt) hipLaunchKernelGGL((decode_splitk_kernel<64, true, false>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((decode_splitk_kernel<64, false, false>), grid, dim3(256), 0, s, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
   CombineArgs ca;
-  ca.partials = c.partials;
-  ca.sp = a.sp;
+  ca.partials = a.partials;
+  ca.table = a.table;
   ca.hq = cfg.n_q_heads;
   ca.group = a.group;
   ca.qblocks = a.qblocks;
@@ -520,6 +616,9 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   ca.out_fp32 = cfg.out_dtype;
   ca.scale_log2 = a.scale_log2;
   ca.out = out;
+  ca.bump = a.sp.bump;
+  ca.capacity = cache.capacity;
+  ca.kv_len_rw = cache.kv_len;
   const dim3 cgrid(cfg.n_q_heads, cache.batch);
   if (cfg.head_dim == 128) hipLaunchKernelGGL(decode_combine_kernel<128>, cgrid, dim3(128), 0, s, ca);
   else hipLaunchKernelGGL(decode_combine_kernel<64>, cgrid, dim3(64), 0, s, ca);

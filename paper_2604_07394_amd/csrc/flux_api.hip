@@ -280,7 +280,24 @@ int flux_attn_decode(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, int
   const DecodePlan p = plan_decode(*cfg, cache->batch, max_kv_len);
   if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
-  const hipError_t e = launch_decode(ctx->c, *cfg, q, max_kv_len, *cache, mode, 0, out, (hipStream_t)stream);
+  const hipError_t e = launch_decode(ctx->c, *cfg, q, max_kv_len, *cache, mode, 0, nullptr, nullptr, out, (hipStream_t)stream);
+  return e == hipSuccess ? FLUX_OK : hip_fail(e);
+}
+
+int flux_attn_decode_append(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const void* k_new, const void* v_new,
+                            int max_kv_len, const flux_kv_cache* cache, const uint8_t* mode, void* out, void* stream) {
+  if (!ctx || !q || !k_new || !v_new || !mode || !out) return FLUX_EINVAL;
+  int rc = check_cfg(cfg);
+  if (rc != FLUX_OK) return rc;
+  rc = check_cache(cache, cfg->head_dim);
+  if (rc != FLUX_OK) return rc;
+  if (max_kv_len < 1) return FLUX_EINVAL;                    // every list holds at least the appended row
+  if (max_kv_len > cache->capacity) return FLUX_ECAPACITY;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(k_new) || !aligned16(v_new)) return FLUX_EINVAL;
+  const DecodePlan p = plan_decode(*cfg, cache->batch, max_kv_len);
+  if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
+  if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
+  const hipError_t e = launch_decode(ctx->c, *cfg, q, max_kv_len, *cache, mode, 0, k_new, v_new, out, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
 }
 
@@ -308,7 +325,7 @@ int flux_attn_decode_static(const flux_attn_cfg* cfg, const void* q, int max_kv_
   c.status = status ? status : (uint32_t*)base;
   c.partials = (float*)(base + kStaticHeader);
   c.partials_bytes = FLUX_STATIC_SCRATCH_BYTES - kStaticHeader;
-  const hipError_t e = launch_decode(c, *cfg, q, max_kv_len, *cache, mode, 0, out, (hipStream_t)stream);
+  const hipError_t e = launch_decode(c, *cfg, q, max_kv_len, *cache, mode, 0, nullptr, nullptr, out, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
 }
 
@@ -363,7 +380,7 @@ int flux_attn_decode_ring(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q
   const DecodePlan p = plan_decode(*cfg, ring->batch, n_keys);
   if (ctx->c.device >= 0 && decode_partials_bytes(*cfg, p) > ctx->c.partials_bytes) return FLUX_EWORKSPACE;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
-  const hipError_t e = launch_decode(ctx->c, *cfg, q, n_keys, *ring, nullptr, 1, out, (hipStream_t)stream);
+  const hipError_t e = launch_decode(ctx->c, *cfg, q, n_keys, *ring, nullptr, 1, nullptr, nullptr, out, (hipStream_t)stream);
   return e == hipSuccess ? FLUX_OK : hip_fail(e);
 }
 

@@ -89,10 +89,11 @@ struct DecodePlan {
   int units;        // workgroups launched: an upper bound on the units of the split the device takes
   int pps;          // (KV head, query block) pairs per sequence
   int rpu;          // partial rows each unit writes
+  int table_floats; // 4-byte words in front of the partial rows that hold the split table (2 per sequence, rounded to 256 B)
 };
 // The split-K decode cuts the visible keys of a call into about kTargetUnits workgroups of at least kMinChunk keys
 // (the split itself is taken on the device; the host only bounds it).
-constexpr int kTargetShift = 10;                // about 1024 workgroups: 4 per CU, two rounds of the two that fit a CU
+constexpr int kTargetShift = 10;                // about 1024 workgroups: 4 per CU (three fit a CU at once)
 constexpr int kTargetUnits = 1 << kTargetShift;
 constexpr int kMinChunk = 256;                  // 64 keys per wave: keeps the per-chunk merge a small part of the streaming
 inline DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len) {
@@ -106,13 +107,18 @@ inline DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_le
   const long long by_len = pairs * (((long long)(max_kv_len > 0 ? max_kv_len : 1) + kMinChunk - 1) / kMinChunk);
   const long long by_target = kTargetUnits + pairs;
   p.units = (int)(by_len < by_target ? by_len : by_target);
+  if (p.units < 1) p.units = 1;                  // one workgroup always runs: it writes the split table
+  p.table_floats = (2 * batch + 63) / 64 * 64;
   return p;
 }
 inline size_t decode_partials_bytes(const flux_attn_cfg& cfg, const DecodePlan& p) {
-  return (size_t)p.units * p.rpu * (cfg.head_dim + 2) * sizeof(float);
+  return ((size_t)p.table_floats + (size_t)p.units * p.rpu * (cfg.head_dim + 2)) * sizeof(float);
 }
+// k_new / v_new != nullptr: the fused decode step (append one row per sequence, then attend: two launches instead of
+// three); needs c.counters and a cache that is not a ring.
 hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, int max_kv_len,
-                         const flux_kv_cache& cache, const uint8_t* mode, int ring, void* out, hipStream_t s);
+                         const flux_kv_cache& cache, const uint8_t* mode, int ring, const void* k_new,
+                         const void* v_new, void* out, hipStream_t s);
 
 // Keep flags of the block-sparse prefill: [batch, heads, n_qblocks, n_kblocks] bytes, heads = 1 or n_q_heads.
 struct BlockMask {

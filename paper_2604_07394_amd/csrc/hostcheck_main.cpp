@@ -45,6 +45,11 @@ int main() {
   EXPECT(flux_attn_prefill(ctx, &cfg, buf + 4, pi, 8, 32, &kc, pb, p, nullptr), FLUX_EINVAL);
   EXPECT(flux_attn_decode(ctx, &cfg, p, -1, &kc, pb, p, nullptr), FLUX_EINVAL);
   EXPECT(flux_attn_decode(ctx, &cfg, p, INT_MAX, &kc, pb, p, nullptr), FLUX_ECAPACITY);
+  EXPECT(flux_attn_decode_append(ctx, &cfg, p, p, p, 32, &kc, pb, p, nullptr), FLUX_EHIP);
+  EXPECT(flux_attn_decode_append(ctx, &cfg, p, p, p, 0, &kc, pb, p, nullptr), FLUX_EINVAL);
+  EXPECT(flux_attn_decode_append(ctx, &cfg, p, nullptr, p, 32, &kc, pb, p, nullptr), FLUX_EINVAL);
+  EXPECT(flux_attn_decode_append(ctx, &cfg, p, p, buf + 4, 32, &kc, pb, p, nullptr), FLUX_EINVAL);
+  EXPECT(flux_attn_decode_append(ctx, &cfg, p, p, p, INT_MAX, &kc, pb, p, nullptr), FLUX_ECAPACITY);
   // extreme sink / window / block sizes: the rounding must not overflow (UBSan watches the arithmetic)
   const int big[] = {1, 63, 64, 65, 1 << 30, INT_MAX - 65536, INT_MAX - 1, INT_MAX};
   const int blocks[] = {0, 1, 2, 64, 4096, 65536};
@@ -53,6 +58,7 @@ int main() {
       for (int b : blocks) {
         flux_attn_cfg c2 = {8, 2, 128, s, w, 0.f, 1, b};
         EXPECT(flux_attn_decode(ctx, &c2, p, 32, &kc, pb, p, nullptr), FLUX_EHIP);
+        EXPECT(flux_attn_decode_append(ctx, &c2, p, p, p, 32, &kc, pb, p, nullptr), FLUX_EHIP);
         EXPECT(flux_attn_prefill(ctx, &c2, p, pi, 8, 32, &kc, pb, p, nullptr), FLUX_EHIP);
         EXPECT(flux_workspace_needed(&c2, 3, 1 << 20) > 0, 1);
         const int rc = flux_attn_decode_ring(ctx, &c2, p, &kc, p, nullptr);

@@ -104,6 +104,15 @@ def test_attention_argument_validation(F, nodev):
     assert rc_of(F, F.flux_attn_decode, *dargs(mk=100)) == F.FLUX_ECAPACITY
     assert rc_of(F, F.flux_attn_decode, *dargs(cfg=F.attn_cfg(8, 0, 128, 4, 16))) == F.FLUX_EINVAL
 
+    # the fused decode step: the arguments of flux_attn_decode plus the appended rows
+    fargs = lambda cfg=good, cache=kc, mk=32, kn=8192, vn=12288: (nodev, cfg, 4096, kn, vn, mk, cache, 512, 1024)
+    assert rc_of(F, F.flux_attn_decode_append, *fargs()) == F.FLUX_EHIP
+    assert rc_of(F, F.flux_attn_decode_append, *fargs(mk=0)) == F.FLUX_EINVAL      # the appended row is always attended
+    assert rc_of(F, F.flux_attn_decode_append, *fargs(mk=100)) == F.FLUX_ECAPACITY
+    assert rc_of(F, F.flux_attn_decode_append, *fargs(kn=None)) == F.FLUX_EINVAL
+    assert rc_of(F, F.flux_attn_decode_append, *fargs(vn=12296)) == F.FLUX_EINVAL  # 16-byte alignment
+    assert rc_of(F, F.flux_attn_decode_append, *fargs(cfg=F.attn_cfg(8, 3, 128, 4, 16))) == F.FLUX_EINVAL
+
 
 def test_append_and_router_argument_validation(F, nodev):
     kc = cache_struct(F)

@@ -197,6 +197,60 @@ def main():
             roofline["traffic"], roofline["traffic_note"] = measured_traffic(
                 "prefill_fa_stack_prefill_32768", ["prefill.hip", "flux_internal.h"])
 
+        # ---- block-sparse prefill over an explicit keep matrix of 64 x 64 blocks, and the XA block selection that
+        # writes such a matrix (layer 0's tensors, one keep matrix per query head)
+        if args.mask == "mix":
+            nb = (S + 63) // 64
+            caches[0].kv_len.zero_()
+            F.flux_kv_append(ctx, caches[0], HKV, D, kn[0], vn[0], cu, S, S)
+
+            def timed(fn, reps=3):
+                fn()
+                es = []
+                for _ in range(reps):
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    fn()
+                    e1.record()
+                    es.append((e0, e1))
+                torch.cuda.synchronize()
+                return sum(a.elapsed_time(b) for a, b in es) / reps
+
+            tri = torch.tril(torch.ones(nb, nb, dtype=torch.bool, device=dev), -1)
+            eye = torch.eye(nb, dtype=torch.bool, device=dev)
+
+            def visible_pairs(keep):                              # keep: uint8 [1, HQ, nb, nb]; whole prompt, S % 64 == 0
+                k = keep[0].bool()
+                return int((k & tri).sum().item()) * 64 * 64 + HQ * nb * (64 * 65 // 2)
+
+            bs = {"block": 64, "blocks_per_side": nb, "fa_kernel_ms": fa_avg}
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(SEED)
+            for dens in (0.10, 0.25):
+                keep = torch.rand(1, HQ, nb, nb, device=dev, generator=gen) < dens
+                keep[..., 0] = True                               # the block of the first positions, as a sink
+                keep = ((keep & tri) | eye).to(torch.uint8).contiguous()
+                ms = timed(lambda: F.flux_attn_prefill_blocksparse(ctx, cfg, q[0], cu, S, S, caches[0], modes[0], keep,
+                                                                   HQ, nb, nb, out))
+                fl = 4.0 * D * visible_pairs(keep)
+                bs["random_keep_%.2f" % dens] = {"kept_fraction_of_causal_blocks": float(keep.sum().item()) / (HQ * nb * (nb + 1) / 2),
+                                                 "kernel_ms": ms, "tflops_over_kept_pairs": fl / (ms * 1e-3) / 1e12,
+                                                 "speedup_vs_fa_launch": fa_avg / ms}
+            xa_keep = torch.zeros(1, HQ, nb, nb, dtype=torch.uint8, device=dev)
+            for thr in (0.9, 0.5):
+                ms_sel = timed(lambda: F.flux_xa_select(ctx, cfg, q[0], cu, S, S, caches[0], 16, thr, xa_keep, nb, nb))
+                ms = timed(lambda: F.flux_attn_prefill_blocksparse(ctx, cfg, q[0], cu, S, S, caches[0], modes[0], xa_keep,
+                                                                   HQ, nb, nb, out))
+                fl = 4.0 * D * visible_pairs(xa_keep)
+                bs["xa_threshold_%.1f" % thr] = {"select_ms": ms_sel, "kept_fraction_of_causal_blocks": float(xa_keep.sum().item()) / (HQ * nb * (nb + 1) / 2),
+                                                 "kernel_ms": ms, "tflops_over_kept_pairs": fl / (ms * 1e-3) / 1e12,
+                                                 "select_plus_kernel_vs_fa_launch": fa_avg / (ms_sel + ms)}
+            bs["note"] = ("seeded Gaussian queries and keys carry no attention structure, so the XA selection keeps most "
+                          "blocks; the random keep matrices show the kernel at the densities a structured prompt gives")
+            prefill["blocksparse"] = bs
+            del keep, xa_keep, tri, eye
+
         # ---- CPU oracle on a bounded sample of the same workload (rank 0, N = 1)
         if not args.no_cpu_baseline:
             from oracle import flux_oracle as O

@@ -39,7 +39,8 @@ struct XaArgs {
   int64_t stride_b, stride_h, stride_t;   // elements
   const int32_t* kv_len;
   int capacity;
-  int hq, group;
+  int hq, group, batch;
+  int n_groups;           // workgroups per (sequence, head): groups of 4 query blocks
   float scale;            // softmax scale (not in log2 units)
   float threshold;
   uint8_t* mask;          // [B, Hq, n_qblocks, n_kblocks]
@@ -61,7 +62,27 @@ __global__ __launch_bounds__(256) void xa_select_kernel(XaArgs a) {
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
   const int g = l >> 4, nn = l & 15;
-  const int grp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  // ---- which (sequence, head, group of 4 query blocks) this workgroup owns.  Workgroups go to the 8 XCDs round-robin
+  // by linear id and every XCD has its own L2: all heads and groups that read one (sequence, KV head) pair get ids of
+  // one residue mod 8, longest walks first and the heads of a GQA group next to each other, so that the workgroups
+  // resident on an XCD walk the same key rows at about the same time and the rows reach that L2 once.
+  int grp, h, b;
+  {
+    const int i = blockIdx.x;
+    const int hkv = a.hq / a.group, n_pairs = a.batch * hkv;
+    if ((n_pairs & 7) == 0) {
+      const int x = i & 7, j = i >> 3, per = n_pairs >> 3;
+      const int gh = j % a.group, r = (j / a.group) % per, gd = j / (a.group * per);
+      const int pair = x + 8 * r;
+      b = pair / hkv;
+      h = (pair % hkv) * a.group + gh;
+      grp = a.n_groups - 1 - gd;
+    } else {
+      grp = a.n_groups - 1 - i % a.n_groups;
+      h = (i / a.n_groups) % a.hq;
+      b = i / (a.n_groups * a.hq);
+    }
+  }
   const int kvh = h / a.group;
 
   const int q_begin = a.cu_q[b];
@@ -251,6 +272,7 @@ hipError_t launch_xa_select(const Ctx& c, const flux_attn_cfg& cfg, const void* 
   a.capacity = cache.capacity;
   a.hq = cfg.n_q_heads;
   a.group = cfg.n_q_heads / cfg.n_kv_heads;
+  a.batch = cache.batch;
   a.scale = cfg.softmax_scale != 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.head_dim);
   a.threshold = threshold;
   a.mask = mask;
@@ -259,7 +281,8 @@ hipError_t launch_xa_select(const Ctx& c, const flux_attn_cfg& cfg, const void* 
   a.status = c.status;
   const int groups = (n_qblocks + 3) / 4;                 // every row of the matrix is written
   (void)max_q_len;
-  const dim3 grid(groups, cfg.n_q_heads, cache.batch);
+  a.n_groups = groups;
+  const dim3 grid((unsigned)((long long)groups * cfg.n_q_heads * cache.batch));
   const size_t lds = xa_select_lds_bytes(n_kblocks);
   if (cfg.head_dim == 128) {
     if (lds > 48 * 1024) {

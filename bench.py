@@ -393,7 +393,7 @@ def main():
         td_fa = time_decode(np.ones(LD, dtype=np.uint8), half, 2) if args.mask == "mix" else None
         kv_len.fill_(N)
         cur["n"] = N
-        td_mix_3 = time_decode(mask_d, half, 2, fused=False) if args.mask == "mix" else None
+        td_mix_3 = time_decode(mask_d, args.decode_steps, args.decode_warmup, fused=False) if args.mask == "mix" else None
         # ---- sparse-decode residency (Sec. 3.3): the SA layers keep only sinks + window rows in a ring cache,
         # compacted from the full cache as after a prefill; FA layers keep the full cache
         ring_info = None

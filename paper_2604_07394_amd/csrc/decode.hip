@@ -152,7 +152,7 @@ __device__ __forceinline__ Split find_split(const SplitArgs& s, int lane, int un
     }
     pieces += __builtin_amdgcn_readlane(wave_inclusive_sum((nv + 127) >> 7), 63);
   }
-  const long long c128 = ((long long)pieces * s.pps + (kTargetUnits - 1)) >> kTargetShift;
+  const long long c128 = ((long long)pieces * s.pps + (kTargetUnits - 1)) / kTargetUnits;
   r.chunk = c128 * 128 < kMinChunk ? kMinChunk : (int)(c128 * 128);
   // If a chunk of about twice that size cuts the batch into one nearly full round of the workgroups the chip
   // holds at once, take it: a single round of equal workgroups pays the start and the merge of a workgroup

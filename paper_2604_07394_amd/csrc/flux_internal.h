@@ -93,8 +93,7 @@ struct DecodePlan {
 };
 // The split-K decode cuts the visible keys of a call into about kTargetUnits workgroups of at least kMinChunk keys
 // (the split itself is taken on the device; the host only bounds it).
-constexpr int kTargetShift = 10;                // about 1024 workgroups: 4 per CU (three fit a CU at once)
-constexpr int kTargetUnits = 1 << kTargetShift;
+constexpr int kTargetUnits = 1024;              // about that many workgroups: 4 per CU (three fit a CU at once)
 constexpr int kMinChunk = 256;                  // 64 keys per wave: keeps the per-chunk merge a small part of the streaming
 inline DecodePlan plan_decode(const flux_attn_cfg& cfg, int batch, int max_kv_len) {
   // Upper bound on the units the device-side split can produce: kTargetUnits + one per pair from the chunk

@@ -260,8 +260,8 @@ int flux_xa_select(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const
   if (!aligned16(q)) return FLUX_EINVAL;
   if (n_qblocks < 1 || n_kblocks < 1 || n_kblocks > kXaMaxKBlocks) return FLUX_EINVAL;
   if ((long long)n_kblocks * 64 < max_kv_len || (long long)n_qblocks * 64 < max_q_len) return FLUX_EINVAL;
-  // one workgroup per (sequence, head, 4 query blocks), on a one-dimensional grid
-  if ((long long)((n_qblocks + 3) / 4) * cfg->n_q_heads * cache->batch > 0x7FFFFFFFll) return FLUX_EINVAL;
+  // one workgroup per (sequence, head, 8 query blocks), on a one-dimensional grid
+  if ((long long)((n_qblocks + 7) / 8) * cfg->n_q_heads * cache->batch > 0x7FFFFFFFll) return FLUX_EINVAL;
   if (ctx->c.device < 0) return hip_fail(hipErrorNoDevice);
   const hipError_t e = launch_xa_select(ctx->c, *cfg, q, cu_q, max_q_len, *cache, threshold, block_mask, n_qblocks,
                                         n_kblocks, (hipStream_t)stream);

@@ -2,14 +2,15 @@
 // one query; the decode step of Sec. 3.3 / App. B.3).
 //
 // Decode is bound by reading the K and V rows of the cache once from HBM.  The work of one
-// (sequence, KV head) pair is cut into chunks of the VISIBLE key list (FA: all positions; SA: the
-// sinks followed by the window tail, so the hidden middle of the cache is never addressed).  One
-// 256-thread workgroup owns one chunk and serves all query heads of the GQA group at once, so every
-// K/V row is fetched exactly once per step.
+// (sequence, KV head) pair is the VISIBLE key list (FA: all positions; SA: the sinks followed by the
+// window tail, so the hidden middle of the cache is never addressed), taken in blocks of 128 keys that
+// go round the pair's units.  One 256-thread workgroup is one unit and serves all query heads of the GQA
+// group at once, so every K/V row is fetched exactly once per step.
 //
 // The split is taken ON THE DEVICE from the lengths and mode bytes the call finds there: the chunk
-// size is the one that cuts the visible keys of the whole batch into about kTargetUnits workgroups,
-// and workgroup u finds its (sequence, KV head, chunk) by a prefix sum over the batch.  Every
+// size (the keys one unit takes) is the one that cuts the visible keys of the whole batch into about
+// kTargetUnits workgroups, a pair of nv visible keys gets ceil(nv / chunk) units, and workgroup u finds
+// its (sequence, KV head, unit of the pair) by a prefix sum over the batch.  Every
 // workgroup with work therefore sits at the front of the grid whatever the mix of lengths and
 // modes in the batch, and a ragged batch fills the chip like a uniform one (a grid shaped by the
 // longest sequence leaves most workgroups of the short ones empty and the rest badly spread).
@@ -24,8 +25,8 @@
 //                                            V operand needs keys along the lane's registers, so V
 //                                            rows are staged in wave-private LDS and read back with
 //                                            the transposing LDS read
-// The four waves keep private (m, l, O) and are merged through LDS at the end; the chunk's
-// unnormalised result goes to the workspace and a second small kernel merges the chunks in a fixed
+// The four waves keep private (m, l, O) and are merged through LDS at the end; the unit's
+// unnormalised result goes to the workspace and a second small kernel merges the units of a pair in a fixed
 // order (deterministic, no float atomics).
 #include "flux_internal.h"
 
@@ -283,7 +284,7 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   // behind for the merge kernel, which then needs neither the lengths nor the scan
   if (unit == (int)gridDim.x - 1 && w == 0) write_split_table(a.sp, l, sp.chunk, a.table);
   if (sp.b < 0) return;                                     // past the last unit: uniform for the whole workgroup
-  const int b = sp.b, chunk = sp.chunk;
+  const int b = sp.b;
   const int local = unit - sp.first_unit;                   // < pps * nc, chunk index fastest
   const int ci = local % sp.nc;
   const int pair = local / sp.nc;
@@ -293,8 +294,13 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   bool bad_b = false, sparse;
   int s_end, tail_start;
   const int n_vis = seq_visible(a.sp, sp.len, sp.md, bad_b, sparse, s_end, tail_start);
-  const int c0 = ci * chunk;
-  const int c1 = min(c0 + chunk, n_vis);
+  // The chunk size fixes how many units a pair has (sp.nc); the pair's 128-key blocks then go round its units: unit ci
+  // takes the blocks ci, ci + nc, ci + 2 nc, ...  Every unit of a pair gets the same number of blocks to within one
+  // (chunks of consecutive keys leave the last unit of every pair a remainder, which costs a ragged batch a tenth of
+  // its time), and the units of a pair, which run side by side, read one moving window of consecutive rows.
+  const int c0 = ci * 128;
+  const int c1 = n_vis;
+  const int pstep = 128 * sp.nc;
   const int tail0 = tail_start - s_end;                     // list index p >= s_end maps to key p + tail0
   // ring store (s_end = sink_lim when sparse): that key sits in row sink_lim + (p + tail0 - sink_lim) % ring_window
   //                                                               = sink_lim + (p - sink_lim + ring0) % ring_window
@@ -313,7 +319,7 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
       new_key = sp.len - 1;
       knew = a.k_new + ((int64_t)b * a.hkv + kvh) * D;
       vnew = a.v_new + ((int64_t)b * a.hkv + kvh) * D;
-      if (ci == sp.nc - 1 && qb == 0 && tid < 2 * CPR) {     // this unit owns the end of the list: it stores the row
+      if (ci == ((n_vis - 1) >> 7) % sp.nc && qb == 0 && tid < 2 * CPR) {   // this unit owns the list's last block: it stores the row
         const int c = tid % CPR;
         const __bf16* src = (tid < CPR ? knew : vnew) + 8 * c;
         __bf16* dst = const_cast<__bf16*>(tid < CPR ? kbase : vbase) + (int64_t)new_key * a.stride_t + 8 * c;
@@ -338,7 +344,7 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   }
 
   auto key_of = [&](int p) -> int64_t {
-    p = p < c1 ? p : c1 - 1;                                // keep every address inside the chunk
+    p = p < c1 ? p : c1 - 1;                                // keep every address inside the list
     if (!sparse || p < s_end) return (int64_t)p;
     if (!a.sp.ring) return (int64_t)p + tail0;
     const int x = p - s_end + ring0;                        // < 2 * ring_window
@@ -411,7 +417,7 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
     for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) kf[sb][kc] = __builtin_bit_cast(bf16x8, kreg[sb][kc]);
-    const int pnext = p0 + 128;
+    const int pnext = p0 + pstep;
     // ---- scores: s[sb][i] is key p0 + 16*sb + 4*g + i against query n
     f32x4 s[2];
 #pragma unroll

@@ -199,6 +199,29 @@ def test_long_context_decode_shape_one_layer(F, G, ctx):
         H.assert_close(H.torch_to_f64(o_ring[b, kvh * g:(kvh + 1) * g]), ref, f"ring decode at full size, seq {b} kv head {kvh}")
     assert F.flux_last_device_status(ctx) == 0
 
+    # ---- the call bench.py times for a layer of a decode step: flux_attn_decode_append with bf16 output (the new
+    # row of every sequence is appended inside the call).  One step as an FA layer, one as an SA layer.
+    for step, (mode, bound) in enumerate(((FA, N + 3), (SA, NS + W)), start=2):
+        G.fill_normal_bf16(kd, SEED, synth.stream_id(synth.STREAM_KDEC, 0, step))
+        G.fill_normal_bf16(vd, SEED, synth.stream_id(synth.STREAM_VDEC, 0, step))
+        G.fill_normal_bf16(qd, SEED, synth.stream_id(synth.STREAM_QDEC, 0, step))
+        o16 = torch.full((B, HQ, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        F.flux_attn_decode_append(ctx, cfg16, qd[0, 0], kd[0, 0], vd[0, 0], bound, cache, u8([mode] * B), o16)
+        torch.cuda.synchronize()
+        n_now = N + step + 1
+        assert kv_len.cpu().tolist() == [n_now] * B
+        assert torch.equal(kc[:, :, n_now - 1].reshape(B * HKV, D), kd[0, 0])
+        assert torch.equal(vc[:, :, n_now - 1].reshape(B * HKV, D), vd[0, 0])
+        q = qd[0, 0].view(B, HQ, D)
+        for b, kvh in ((0, 5), (3, 0), (5, 7), (7, 3)):
+            kf = H.torch_to_f64(kc[b, kvh, :n_now])
+            vf = H.torch_to_f64(vc[b, kvh, :n_now])
+            ref = O.attention_row(H.torch_to_f64(q[b, kvh * g:(kvh + 1) * g]), kf, vf, n_now - 1, mode, NS, W)
+            got16 = H.torch_to_f64(o16[b, kvh * g:(kvh + 1) * g])
+            assert np.isfinite(got16).all()
+            assert (np.abs(got16 - ref) <= np.maximum(1e-2, 2.0 ** -8 * np.abs(ref))).all(), (step, b, kvh)
+    assert F.flux_last_device_status(ctx) == 0
+
 
 def test_high_sparsity_prefill_shape(F, G, ctx):
     """High-sparsity prefill workload, one SA and one FA layer: batch 2, 65536 tokens, 28/4 heads (group

@@ -407,39 +407,20 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 
     FLUX_LDS char* st = (FLUX_LDS char*)smem + STG * STAGE;
     // Order of the block, written out so that every LDS read is issued well before its use (the fences keep
-    // the compiler from sinking the reads back to their uses):
-    //   K fragments of both halves | S^T half 0 | V fragments of half 0 | S^T half 1 | weights |
-    //   V fragments of half 1 | O^T += half 0 | O^T += half 1
+    // the compiler from moving the reads):
+    //   K fragments of half 0 | S^T half 0, the K fragments of half 1 read between its MFMAs |
+    //   S^T half 1, the V fragments of half 0 read between its MFMAs | weights |
+    //   O^T += half 0, the V fragments of half 1 read between its MFMAs | O^T += half 1
     f32x4 s[KB][2];              // s[kb][qb][i]: key j0 + 16*kb + 4*g + i against query row (qb, n)
     bf16x8 pf[2][KS];            // pf[qb][ks]: weights of keys 32*ks + {4g..4g+3, 16+4g..16+4g+3}, as a B operand
     bf16x8 kf[KB][KC];
     bf16x8 vf[KS][DB];
-    auto load_k = [&](int ks) {
-#pragma unroll
-      for (int kb = 2 * ks; kb < 2 * ks + 2; ++kb)
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) kf[kb][kc] = *(FLUX_LDS bf16x8*)(st + k_rd[kc] + 16 * kb * KPITCH);
-    };
-    auto load_v = [&](int ks) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        FLUX_LDS char* vp = st + v_rd[db] + 32 * ks * ROWB;
-        const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)vp);
-        const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)(vp + 16 * ROWB));
-        vf[ks][db] = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-      }
-    };
-    auto scores = [&](int ks) {
-#pragma unroll
-      for (int kb = 2 * ks; kb < 2 * ks + 2; ++kb) {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) s[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kc], qf[qb][kc], s[kb][qb], 0, 0, 0);
-      }
+    auto read_k = [&](int kb, int kc) { kf[kb][kc] = *(FLUX_LDS bf16x8*)(st + k_rd[kc] + 16 * kb * KPITCH); };
+    auto read_v = [&](int ks, int db) {
+      FLUX_LDS char* vp = st + v_rd[db] + 32 * ks * ROWB;
+      const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)vp);
+      const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FLUX_LDS bf16x4*)(vp + 16 * ROWB));
+      vf[ks][db] = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
     };
     // Softmax weights against the reference m_ref the accumulators already refer to, WITHOUT looking for the
     // block's maximum first: any reference gives the same quotient, and fp32 / bf16 keep their relative
@@ -525,15 +506,35 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       }
       if (skip) return;
     }
-    load_k(0);
-    load_k(1);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) read_k(kb, kc);
     __builtin_amdgcn_sched_barrier(0);
-    scores(0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(0);
-    __builtin_amdgcn_sched_barrier(0);
-    scores(1);
-    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) s[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // S^T of keys 0..31 with the K fragments of keys 32..63 read between the MFMAs, then S^T of keys 32..63 with the V
+    // fragments of keys 0..31 read between them: a read between two MFMAs costs the wave a few cycles, in a run of
+    // reads sixteen, and every fragment is asked for at least sixteen MFMAs before its use
+#pragma unroll
+    for (int t = 0; t < 2 * KC; ++t) {
+      const int kc = t >> 1, kb = t & 1;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kc], qf[qb][kc], s[kb][qb], 0, 0, 0);
+      read_k(2 + kb, kc);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int t = 0; t < 2 * KC; ++t) {
+      const int kc = t >> 1, kb = 2 + (t & 1);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kc], qf[qb][kc], s[kb][qb], 0, 0, 0);
+#pragma unroll
+      for (int db = t * DB / (2 * KC); db < (t + 1) * DB / (2 * KC); ++db) read_v(0, db);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // Element masks.  Key j = j0 + 4*g + c with the constant c = 16*kb + i, so each bound is moved into the
     // lane once (bound - j0 - 4*g) and compared with constants.
     if (mask_edge) {
@@ -568,10 +569,14 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     weights_guarded();
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
-    load_v(1);
-    __builtin_amdgcn_sched_barrier(0);
-    accumulate(0);
-    __builtin_amdgcn_sched_barrier(0);
+    // O^T += keys 0..31 with the V fragments of keys 32..63 read between the MFMAs
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[0][db], pf[qb][0], o[db][qb], 0, 0, 0);
+      read_v(1, db);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     accumulate(1);
   };
 

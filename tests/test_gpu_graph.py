@@ -1,6 +1,7 @@
 """The hot calls are plain kernel launches on the caller's stream: a decode step (append + attention for a
-few layers, one of them on a ring cache) can be captured into a HIP graph once and replayed, with the
-program's own eager work between replays.  Every replay is checked against the oracle."""
+few layers: one through the fused call, one through the two calls, one on a ring cache) can be captured into a HIP
+graph once and replayed, with the program's own eager work between replays.  Every replay is checked against the
+oracle."""
 import numpy as np
 import pytest
 import torch
@@ -60,6 +61,8 @@ def test_decode_step_replays_from_a_graph(F):
             if modes[l] is None:
                 F.flux_kv_append_ring(ctx, caches[l], hkv, d, n_sink, window, k_in[l], v_in[l], cu_b, B, 1)
                 F.flux_attn_decode_ring(ctx, cfg, q_in[l], caches[l], out[l])
+            elif l == 0:                                         # the decode step of a layer as one call
+                F.flux_attn_decode_append(ctx, cfg, q_in[l], k_in[l], v_in[l], 800, caches[l], mode_dev[l], out[l])
             else:
                 F.flux_kv_append(ctx, caches[l], hkv, d, k_in[l], v_in[l], cu_b, B, 1)
                 F.flux_attn_decode(ctx, cfg, q_in[l], 800, caches[l], mode_dev[l], out[l])

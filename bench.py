@@ -237,6 +237,20 @@ def main():
                 bs["random_keep_%.2f" % dens] = {"kept_fraction_of_causal_blocks": float(keep.sum().item()) / (HQ * nb * (nb + 1) / 2),
                                                  "kernel_ms": ms, "tflops_over_kept_pairs": fl / (ms * 1e-3) / 1e12,
                                                  "speedup_vs_fa_launch": fa_avg / ms}
+            # the same densities as whole key columns per head (every query block keeps the same key blocks) plus the
+            # four most recent blocks: the shape attention maps usually have (vertical stripes and a local band), where
+            # the query blocks of a 128-row tile agree on what they visit
+            band = torch.tril(torch.ones(nb, nb, dtype=torch.bool, device=dev)) & ~torch.tril(torch.ones(nb, nb, dtype=torch.bool, device=dev), -4)
+            for dens in (0.10, 0.25):
+                cols = torch.rand(1, HQ, 1, nb, device=dev, generator=gen) < dens
+                cols[..., 0] = True
+                keep = (((cols.expand(1, HQ, nb, nb) & tri) | band)).to(torch.uint8).contiguous()
+                ms = timed(lambda: F.flux_attn_prefill_blocksparse(ctx, cfg, q[0], cu, S, S, caches[0], modes[0], keep,
+                                                                   HQ, nb, nb, out))
+                fl = 4.0 * D * visible_pairs(keep)
+                bs["striped_keep_%.2f" % dens] = {"kept_fraction_of_causal_blocks": float(keep.sum().item()) / (HQ * nb * (nb + 1) / 2),
+                                                  "kernel_ms": ms, "tflops_over_kept_pairs": fl / (ms * 1e-3) / 1e12,
+                                                  "speedup_vs_fa_launch": fa_avg / ms}
             xa_keep = torch.zeros(1, HQ, nb, nb, dtype=torch.uint8, device=dev)
             for thr in (0.9, 0.5):
                 ms_sel = timed(lambda: F.flux_xa_select(ctx, cfg, q[0], cu, S, S, caches[0], 16, thr, xa_keep, nb, nb))
@@ -249,7 +263,7 @@ def main():
             bs["note"] = ("seeded Gaussian queries and keys carry no attention structure, so the XA selection keeps most "
                           "blocks; the random keep matrices show the kernel at the densities a structured prompt gives")
             prefill["blocksparse"] = bs
-            del keep, xa_keep, tri, eye
+            del keep, xa_keep, tri, eye, band
 
         # ---- CPU oracle on a bounded sample of the same workload (rank 0, N = 1)
         if not args.no_cpu_baseline:

@@ -260,6 +260,30 @@ def main():
                 bs["xa_threshold_%.1f" % thr] = {"select_ms": ms_sel, "kept_fraction_of_causal_blocks": float(xa_keep.sum().item()) / (HQ * nb * (nb + 1) / 2),
                                                  "kernel_ms": ms, "tflops_over_kept_pairs": fl / (ms * 1e-3) / 1e12,
                                                  "select_plus_kernel_vs_fa_launch": fa_avg / (ms_sel + ms)}
+            # the same selection on inputs WITH structure: every query leans towards a direction u_h of its head, and the
+            # keys of 8 % of the 64-position blocks (whole columns, per KV head) lean the same way, so most of the
+            # attention mass sits on those columns and on nothing else
+            gq = torch.Generator(device=dev)
+            gq.manual_seed(SEED + 77)
+            u = torch.sign(torch.randn(HKV, D, device=dev, generator=gq))                     # |u|^2 = D
+            qs = torch.randn(S, HQ, D, device=dev, generator=gq) + 0.8 * u.repeat_interleave(G, 0)[None]
+            stripe = (torch.rand(HKV, nb, device=dev, generator=gq) < 0.08).repeat_interleave(64, 1)[:, :S]   # [HKV, S]
+            ks_ = torch.randn(S, HKV, D, device=dev, generator=gq) + 0.8 * stripe.t()[:, :, None] * u[None]
+            vs_ = torch.randn(S, HKV, D, device=dev, generator=gq)
+            qs, ks_, vs_ = qs.to(torch.bfloat16), ks_.to(torch.bfloat16), vs_.to(torch.bfloat16)
+            caches[0].kv_len.zero_()
+            F.flux_kv_append(ctx, caches[0], HKV, D, ks_, vs_, cu, S, S)
+            ms_sel = timed(lambda: F.flux_xa_select(ctx, cfg, qs, cu, S, S, caches[0], 16, 0.9, xa_keep, nb, nb))
+            ms = timed(lambda: F.flux_attn_prefill_blocksparse(ctx, cfg, qs, cu, S, S, caches[0], modes[0], xa_keep,
+                                                               HQ, nb, nb, out))
+            ms_fa = timed(lambda: F.flux_attn_prefill(ctx, cfg, qs, cu, S, S, caches[0], modes[1], out))
+            fl = 4.0 * D * visible_pairs(xa_keep)
+            bs["xa_threshold_0.9_structured_input"] = {
+                "input": "q = N(0,1) + 0.8 u_head, k = N(0,1) + 0.8 u_head on 8 percent of the key blocks (whole columns per KV head), seed %d" % (SEED + 77),
+                "select_ms": ms_sel, "kept_fraction_of_causal_blocks": float(xa_keep.sum().item()) / (HQ * nb * (nb + 1) / 2),
+                "kernel_ms": ms, "tflops_over_kept_pairs": fl / (ms * 1e-3) / 1e12, "fa_kernel_ms_same_input": ms_fa,
+                "select_plus_kernel_vs_fa_launch": ms_fa / (ms_sel + ms)}
+            del qs, ks_, vs_, stripe, u
             bs["note"] = ("seeded Gaussian queries and keys carry no attention structure, so the XA selection keeps most "
                           "blocks; the random keep matrices show the kernel at the densities a structured prompt gives")
             prefill["blocksparse"] = bs

@@ -172,6 +172,9 @@ int flux_attn_prefill_blocksparse(flux_ctx* ctx, const flux_attn_cfg* cfg, const
  * 16; 0 < threshold <= 1; cfg->softmax_scale as in Eq. 1; cfg->n_sink, window, sa_block, out_dtype are not used.
  * block_mask: dev uint8 [batch, n_q_heads, n_qblocks, n_kblocks], every byte written (0 or 1);
  * n_kblocks * 64 >= max_kv_len, n_qblocks * 64 >= max_q_len, n_kblocks <= 4096 (262144 positions), else FLUX_EINVAL.
+ * max_q_len bounds the prompt lengths (host); a prompt found longer on the device is scored up to the bound, rounded
+ * up to whole blocks, and FLUX_DEV_BAD_LENGTH is raised.  Prompts of up to 65536 positions (by that bound) are
+ * scored in one walk over the keys, longer ones in two.
  * The masses are computed in fp32 from exact bf16 products: near a tie between the threshold and a partial sum
  * of masses the selection can differ from one made in higher precision. */
 int flux_xa_select(flux_ctx* ctx, const flux_attn_cfg* cfg, const void* q, const int32_t* cu_q, int max_q_len,

@@ -130,7 +130,11 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
 
 // XA block selection: LDS of one workgroup (partial tiles + the masses of 8 query blocks), and the launcher
 constexpr int kXaMaxKBlocks = 4096;           // key blocks a prompt may have (262144 positions): the masses live in LDS
-inline size_t xa_select_lds_bytes(int n_kblocks) { return (size_t)2 * 4 * 512 * 4 + (size_t)8 * n_kblocks * 4; }
+constexpr int kXaSingleWalkMaxKBlocks = 1024; // up to here the (square row, key block) table of one workgroup fits LDS (144 KB)
+inline size_t xa_select_lds_bytes(int n_kblocks) {
+  const size_t table = n_kblocks <= kXaSingleWalkMaxKBlocks ? (size_t)32 * n_kblocks : (size_t)8 * n_kblocks;
+  return (size_t)2 * 4 * 512 * 4 + table * 4;
+}
 hipError_t launch_xa_select(const Ctx& c, const flux_attn_cfg& cfg, const void* q, const int32_t* cu_q, int max_q_len,
                             const flux_kv_cache& cache, float threshold, uint8_t* mask, int n_qblocks, int n_kblocks,
                             hipStream_t s);

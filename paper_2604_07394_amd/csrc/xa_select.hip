@@ -24,9 +24,13 @@
 //   - the four partial 32 x 16 tiles meet in LDS, where thread (a, b) adds them in wave order.  On the diagonal
 //     the samples r < 8 are not causal: exactly the partial tiles of waves 0 and 1, which are left out there;
 //     positions past the prompt are zeroed in the operands, and the number of samples of a square is a closed form;
-//   - the softmax over a row of squares needs the row's maximum and sum first, so the columns are walked twice:
-//     once for (max, sum), once for the probabilities, which are summed 4 x 4 into the masses (a wave of the
-//     reduction phase holds the 4 square rows of one query block);
+//   - the softmax over a row of squares needs the row's maximum and sum, which are known only at the end of the
+//     row.  Prompts of up to 65536 positions are walked once: of every (square row, key block) the logarithm of
+//     the summed exponentials of its 4 squares is kept in LDS (it needs no reference), and when the row's
+//     log-sum-exp is known the masses are the exponentials of the differences, summed over the 4 rows of a query
+//     block.  Longer prompts (the table would not fit) are walked twice: once for (max, sum), once for the
+//     probabilities, which are summed 4 x 4 into the masses (a wave of the reduction phase holds the 4 square rows
+//     of one query block);
 //   - the threshold is found without sorting: the largest mass value t with sum(mass >= t) >= threshold * total,
 //     by bisection over the bit patterns of the positive floats (32 steps, one row reduction each).
 #include <type_traits>
@@ -48,6 +52,8 @@ struct XaArgs {
   float threshold;
   uint8_t* mask;          // [B, Hq, n_qblocks, n_kblocks]
   int n_qblocks, n_kblocks;
+  int tab_cols;           // key blocks the host's bound on the prompt length allows (<= n_kblocks): the width of the LDS tables
+  int single_walk;        // the (square row, key block) table fits LDS: one walk over the keys
   uint32_t* status;
 };
 
@@ -55,12 +61,16 @@ constexpr int kXaRows = 32;        // square rows per workgroup (512 queries): t
 constexpr int kXaStride = 16;      // positions per square side (Table 3: stride 16)
 
 template <int D>
-__global__ __launch_bounds__(256) void xa_select_kernel(XaArgs a) {
+__global__ __launch_bounds__(256, 2) void xa_select_kernel(XaArgs a) {
   constexpr int ST = D / 8;        // k-steps of 32 numbers per wave: 4 row offsets x D / 32
   constexpr int SPR = D / 32;      // k-steps per row offset
   extern __shared__ __attribute__((aligned(16))) char xa_smem[];
   float* part = (float*)xa_smem;                       // [2 buffers][4 waves][32 a][16 b]
-  float* mass = part + 2 * 4 * 512;                    // [8 query blocks][n_kblocks]
+  float* mass = part + 2 * 4 * 512;                    // [8 query blocks][tab_cols]; one walk: [32 square rows][tab_cols]
+  float* lse = part;                                   // one walk: log-sum-exp of every square row, kept where the partial
+                                                       // tiles were once the walk is over (two workgroups of a 32768-token
+                                                       // prompt then fit the LDS of a CU exactly)
+  const bool single = a.single_walk != 0;
 
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
@@ -94,7 +104,11 @@ __global__ __launch_bounds__(256) void xa_select_kernel(XaArgs a) {
   // the selection is defined for a whole prompt: as many queries as cached positions
   if (grp == 0 && h == 0 && tid == 0 && (len < 0 || len > a.capacity || n_q != len)) atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
   len = len < 0 ? 0 : (len > a.capacity ? a.capacity : len);
-  const int n = n_q < len ? (n_q < 0 ? 0 : n_q) : len;   // positions 0 .. n-1 are scored
+  int n = n_q < len ? (n_q < 0 ? 0 : n_q) : len;         // positions 0 .. n-1 are scored
+  if (n > 64 * a.tab_cols) {                             // a prompt longer than the host's bound: cut there, and say so
+    if (grp == 0 && h == 0 && tid == 0) atomicOr(a.status, (uint32_t)FLUX_DEV_BAD_LENGTH);
+    n = 64 * a.tab_cols;
+  }
   const int a0 = grp * kXaRows;                          // first square row of the workgroup
   uint8_t* mrow0 = a.mask + (((int64_t)b * a.hq + h) * a.n_qblocks + 8 * grp) * (int64_t)a.n_kblocks;
   const int n_sq = (n + kXaStride - 1) / kXaStride;      // square rows / columns of the prompt
@@ -194,6 +208,10 @@ __global__ __launch_bounds__(256) void xa_select_kernel(XaArgs a) {
       float pe = e == -INFINITY ? 0.f : __expf(e - m_new);
       pe += __shfl_xor(pe, 1);
       pe += __shfl_xor(pe, 2);
+      if (single && (rb & 3) == 0) {                                    // the 4 squares of one key block, reference-free
+        const int kbk = 4 * ct + (rb >> 2);
+        if (kbk < a.tab_cols) mass[(16 * ah + ra) * a.tab_cols + kbk] = pe > 0.f ? m_new + __logf(pe) : -INFINITY;
+      }
       pe += __shfl_xor(pe, 4);
       pe += __shfl_xor(pe, 8);
       l_row[ah] = (m_row[ah] == -INFINITY ? 0.f : l_row[ah] * __expf(m_row[ah] - m_new)) + pe;
@@ -221,13 +239,18 @@ __global__ __launch_bounds__(256) void xa_select_kernel(XaArgs a) {
       p += __shfl_xor(p, 32);
       if ((l & 0x33) == 0 && rows_in_block[ah] > 0) {
         const int kbk = 4 * ct + (rb >> 2);
-        if (kbk < a.n_kblocks) mass[(4 * ah + w) * a.n_kblocks + kbk] = p / (float)rows_in_block[ah];
+        if (kbk < a.tab_cols) mass[(4 * ah + w) * a.tab_cols + kbk] = p / (float)rows_in_block[ah];
       }
     }
   };
   __syncthreads();                                                    // the first walk's last readers are done
-  fetch_tile(0);
-  for (int ct = 0; ct < n_ct; ++ct) second_walk(ct);
+  if (!single) {
+    fetch_tile(0);
+    for (int ct = 0; ct < n_ct; ++ct) second_walk(ct);
+  } else if (rb == 0) {
+#pragma unroll
+    for (int ah = 0; ah < 2; ++ah) lse[16 * ah + ra] = m_row[ah] + __logf(l_row[ah]);
+  }
   __syncthreads();
 
   // ---- selection: wave w owns the query blocks 8*grp + w and 8*grp + 4 + w and their masses of key blocks 0 .. own
@@ -246,8 +269,17 @@ __global__ __launch_bounds__(256) void xa_select_kernel(XaArgs a) {
       for (int j = l; j < a.n_kblocks; j += 64) mrow[j] = 0;
       continue;
     }
-    const float* mq = mass + qi * a.n_kblocks;
-    const int nj = min(qb_abs + 1, a.n_kblocks);
+    const int nj = min(qb_abs + 1, a.tab_cols);
+    float* mq = mass + (single ? 4 * qi : qi) * a.tab_cols;
+    if (single) {
+      // masses of this query block from the table, written over its first row (this wave alone touches these rows)
+      const int rows = min(4, n_sq - (a0 + 4 * qi));
+      for (int j = l; j < nj; j += 64) {
+        float acc = 0.f;
+        for (int r = 0; r < rows; ++r) acc += __expf(mq[r * a.tab_cols + j] - lse[4 * qi + r]);
+        mq[j] = acc / (float)rows;
+      }
+    }
     float tot = 0.f, mx = 0.f;
     for (int j = l; j < nj; j += 64) {
       tot += mq[j];
@@ -292,12 +324,14 @@ hipError_t launch_xa_select(const Ctx& c, const flux_attn_cfg& cfg, const void* 
   a.mask = mask;
   a.n_qblocks = n_qblocks;
   a.n_kblocks = n_kblocks;
+  const int need = (max_q_len + 63) / 64;                 // the prompt is the whole cache: its length is bounded by max_q_len
+  a.tab_cols = need < n_kblocks ? (need > 0 ? need : 1) : n_kblocks;
+  a.single_walk = a.tab_cols <= kXaSingleWalkMaxKBlocks;
   a.status = c.status;
   const int groups = (n_qblocks + 7) / 8;                 // every row of the matrix is written
-  (void)max_q_len;
   a.n_groups = groups;
   const dim3 grid((unsigned)((long long)groups * cfg.n_q_heads * cache.batch));
-  const size_t lds = xa_select_lds_bytes(n_kblocks);
+  const size_t lds = xa_select_lds_bytes(a.tab_cols);
   if (cfg.head_dim == 128) {
     if (lds > 48 * 1024) {
       const hipError_t e = hipFuncSetAttribute((const void*)xa_select_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

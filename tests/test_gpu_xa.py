@@ -185,3 +185,35 @@ def test_xa_selection_long_prompt_sampled_rows(F, ctx):
     print("XA selection at 32768 tokens: %.3f ms, %.1f %% of the causal block pairs kept, %d of %d sampled rows differ"
           % (e0.elapsed_time(e1), 100 * dens, differ, total))
     assert F.flux_last_device_status(ctx) == 0
+
+
+def test_xa_selection_beyond_65536_positions_two_walks(F, ctx):
+    """A prompt of 66100 positions: the (square row, key block) table of a workgroup no longer fits LDS, so the kernel
+    walks the keys twice (maximum and sum first, probabilities second).  Sampled rows against the oracle."""
+    S, HQ, HKV, D = 66100, 2, 1, 64
+    from paper_2604_07394_amd import synth_gpu as G
+    q = torch.empty(1, S, HQ, D, dtype=torch.bfloat16, device="cuda")
+    kn = torch.empty(1, S, HKV, D, dtype=torch.bfloat16, device="cuda")
+    G.fill_normal_bf16(q, 95, synth.stream_id(synth.STREAM_Q))
+    G.fill_normal_bf16(kn, 95, synth.stream_id(synth.STREAM_K))
+    cache = F.KVCache.empty(1, HKV, S, D)
+    F.flux_kv_append(ctx, cache, HKV, D, kn[0], kn[0], i32([0, S]), S, S)
+    nb = -(-S // BLK)
+    assert nb > 1024
+    mask = torch.full((1, HQ, nb, nb), 9, dtype=torch.uint8, device="cuda")
+    cfg = F.attn_cfg(HQ, HKV, D, 0, 1, 0.0, 1)
+    F.flux_xa_select(ctx, cfg, q[0], i32([0, S]), S, S, cache, STRIDE, 0.9, mask, nb, nb)
+    torch.cuda.synchronize()
+    got = mask.cpu().numpy()[0].astype(bool)
+    assert mask.max().item() <= 1                                      # every byte written
+    rows = [0, 7, 640, nb - 2, nb - 1]
+    differ = total = 0
+    for h in range(HQ):
+        qf = H.torch_to_f64(q[0, :, h])
+        kf = H.torch_to_f64(kn[0, :, 0])
+        dd, tt = check_selection(got[h:h + 1], qf[:, None, :], kf[:, None, :], 1, 1, 0.9, rows=rows)
+        differ += dd
+        total += tt
+    print("XA selection at %d tokens (two walks): %d of %d sampled rows differ" % (S, differ, total))
+    assert F.flux_last_device_status(ctx) == 0
+

@@ -459,7 +459,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     // redo the weights.  In the steady state the maximum, its cross-lane steps and the rescale are not executed.
     auto weights_guarded = [&]() {
       weights();
-      if (!all_ref || __builtin_amdgcn_ballot_w64(!(l_blk[0] < kWeightGuard) | !(l_blk[1] < kWeightGuard)) != 0) {
+      // (one ballot per comparison: each is then the comparison's own lane mask, with no vector instruction between)
+      if (!all_ref || (__builtin_amdgcn_ballot_w64(!(l_blk[0] < kWeightGuard)) | __builtin_amdgcn_ballot_w64(!(l_blk[1] < kWeightGuard))) != 0) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
           float mloc = s[0][qb][0];
@@ -511,32 +512,33 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) read_k(kb, kc);
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) s[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
     // S^T of keys 0..31 with the K fragments of keys 32..63 read between the MFMAs, then S^T of keys 32..63 with the V
     // fragments of keys 0..31 read between them: a read between two MFMAs costs the wave a few cycles, in a run of
-    // reads sixteen, and every fragment is asked for at least sixteen MFMAs before its use
+    // reads sixteen, and every fragment is asked for at least sixteen MFMAs before its use.  The accumulators start
+    // from what the caller put into s.
+    auto scores = [&]() {
 #pragma unroll
-    for (int t = 0; t < 2 * KC; ++t) {
-      const int kc = t >> 1, kb = t & 1;
+      for (int t = 0; t < 2 * KC; ++t) {
+        const int kc = t >> 1, kb = t & 1;
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kc], qf[qb][kc], s[kb][qb], 0, 0, 0);
-      read_k(2 + kb, kc);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+        for (int qb = 0; qb < 2; ++qb) s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kc], qf[qb][kc], s[kb][qb], 0, 0, 0);
+        read_k(2 + kb, kc);
+        __builtin_amdgcn_sched_barrier(0);
+      }
 #pragma unroll
-    for (int t = 0; t < 2 * KC; ++t) {
-      const int kc = t >> 1, kb = 2 + (t & 1);
+      for (int t = 0; t < 2 * KC; ++t) {
+        const int kc = t >> 1, kb = 2 + (t & 1);
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kc], qf[qb][kc], s[kb][qb], 0, 0, 0);
+        for (int qb = 0; qb < 2; ++qb) s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kc], qf[qb][kc], s[kb][qb], 0, 0, 0);
 #pragma unroll
-      for (int db = t * DB / (2 * KC); db < (t + 1) * DB / (2 * KC); ++db) read_v(0, db);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // Element masks.  Key j = j0 + 4*g + c with the constant c = 16*kb + i, so each bound is moved into the
-    // lane once (bound - j0 - 4*g) and compared with constants.
+        for (int db = t * DB / (2 * KC); db < (t + 1) * DB / (2 * KC); ++db) read_v(0, db);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    // Element masks are put into the accumulators the scores start from: 0 for a visible pair, -inf for a hidden one
+    // (the sum of the products then stays -inf), so a plain block starts from the constant 0 and the scores of either
+    // kind of block come out of the MFMAs in the same registers.  Key j = j0 + 4*g + c with the constant c = 16*kb + i,
+    // so each bound is moved into the lane once (bound - j0 - 4*g) and compared with constants.
     if (mask_edge) {
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
@@ -547,9 +549,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           for (int i = 0; i < 4; ++i) {
             const int c = 16 * kb + i;
             const bool vis = (c <= hi) & ((c < sl) | (c >= lo));
-            s[kb][qb][i] = vis ? s[kb][qb][i] : -INFINITY;
+            s[kb][qb][i] = vis ? 0.f : -INFINITY;
           }
       }
+      scores();
     } else if (mask_causal) {
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
@@ -559,8 +562,15 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) s[kb][qb][i] = 16 * kb + i <= hi ? s[kb][qb][i] : -INFINITY;
+          for (int i = 0; i < 4; ++i) s[kb][qb][i] = 16 * kb + i <= hi ? 0.f : -INFINITY;
       }
+      scores();
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) s[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      scores();
     }
     // The softmax part runs at a raised wave priority: while it is short, the other wave of this SIMD is mostly
     // inside a run of MFMAs, which queue on the matrix pipe anyway, so letting the vector work through first

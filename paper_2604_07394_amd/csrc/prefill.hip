@@ -537,8 +537,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     };
     // Element masks are put into the accumulators the scores start from: 0 for a visible pair, -inf for a hidden one
     // (the sum of the products then stays -inf), so a plain block starts from the constant 0 and the scores of either
-    // kind of block come out of the MFMAs in the same registers.  Key j = j0 + 4*g + c with the constant c = 16*kb + i,
-    // so each bound is moved into the lane once (bound - j0 - 4*g) and compared with constants.
+    // kind of block come out of the MFMAs in the same registers.  (With the masks applied to the finished scores the
+    // compiler keeps masked and unmasked scores in different registers and copies all 32 of them in every plain
+    // block.)  Key j = j0 + 4*g + c with the constant c = 16*kb + i, so each bound is moved into the lane once
+    // (bound - j0 - 4*g) and compared with constants.
     if (mask_edge) {
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {

@@ -77,6 +77,7 @@ __device__ __forceinline__ int window_start(int i, int shift, int win_blocks) {
 constexpr int kCounters = 64;
 constexpr size_t kSmallBytes = 8u << 20;      // router: batch * (splits * hidden + inner) floats
 constexpr size_t kHeaderBytes = 4096;         // status + counters
+constexpr int kPrefillWideMinRows = 32768;    // prefill launches whose longest prompt has at least this many rows use 256-row workgroups
 
 // ---- launchers (each validates nothing: flux_api.hip has done it) ---------------------------
 hipError_t launch_kv_append(const Ctx& c, const flux_kv_cache& cache, int hkv, int d, const void* k_new,

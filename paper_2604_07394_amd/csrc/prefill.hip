@@ -2,7 +2,7 @@
 // sink + window subset of Sec. 4.1 / App. C.3), chosen per sequence by the cached mode byte.
 //
 // Shape of the computation (one workgroup = 128 query rows of one head, 4 waves x 32 rows = 2 column blocks
-// of 16 queries):
+// of 16 queries; launches for long prompts use 8 waves and 256 rows per workgroup, see launch_prefill):
 //   for each VISITED 64-key block (FA: all blocks up to the diagonal; SA: the sink blocks and the
 //   blocks that intersect the tile's window, nothing else: hidden blocks are skipped, not masked)
 //     S^T[key][q]  = K[key][:] . Q[q][:]     MFMA 16x16x32 bf16, A = K rows from LDS, B = Q in registers
@@ -53,7 +53,6 @@ struct PrefillArgs {
   int bm_heads, bm_qblocks, bm_kblocks;
 };
 
-constexpr int BM = 128;   // query rows per workgroup
 constexpr float kWeightGuard = 1073741824.0f;   // 2^30: a block whose weights sum past this moves the softmax reference
 
 // One wave-wide direct global -> LDS transfer: every lane fetches its own 16 bytes, the 64 pieces land
@@ -82,18 +81,19 @@ __device__ __forceinline__ void dma_tile4(const char* kt, const char* vt, const 
                    [o5] "i"(OFF + KT + 4096), [o6] "i"(OFF + KT + 8192), [o7] "i"(OFF + KT + 12288)
                : "memory", "m0", "scc");
 }
-template <int OFF, int KT>
+template <int OFF, int KT, int STEP = 4096>   // STEP: bytes between the two transfers of a wave (1 KB per wave of the workgroup)
 __device__ __forceinline__ void dma_tile2(const char* kt, const char* vt, const int (&ko)[2], const int (&vo)[2],
                                           uint32_t lds_base) {
   asm volatile(FLUX_DMA_ONE("k0", "kt", "o0") FLUX_DMA_ONE("k1", "kt", "o1") FLUX_DMA_ONE("v0", "vt", "o4")
                FLUX_DMA_ONE("v1", "vt", "o5")
                : : [k0] "v"(ko[0]), [k1] "v"(ko[1]), [v0] "v"(vo[0]), [v1] "v"(vo[1]), [kt] "s"(kt), [vt] "s"(vt),
-                   [lds] "s"(lds_base), [o0] "i"(OFF), [o1] "i"(OFF + 4096), [o4] "i"(OFF + KT), [o5] "i"(OFF + KT + 4096)
+                   [lds] "s"(lds_base), [o0] "i"(OFF), [o1] "i"(OFF + STEP), [o4] "i"(OFF + KT), [o5] "i"(OFF + KT + STEP)
                : "memory", "m0", "scc");
 }
 
-template <int D, bool BS>
-__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
+template <int D, bool BS, int NW>   // NW: waves per workgroup, 4 (two workgroups per CU) or 8 (one)
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void prefill_kernel(PrefillArgs a) {
+  constexpr int BM = 32 * NW;             // query rows per workgroup
   constexpr int BN = 64;                  // keys per iteration: two halves of 32, the K dimension of one PV MFMA
   constexpr int KC = D / 32;              // MFMA k-steps over the head dimension (QK^T)
   constexpr int DB = D / 16;              // 16-wide output blocks over the head dimension (PV)
@@ -114,11 +114,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int KTILE = BN * ROWB;
   constexpr int VTILE = BN * ROWB;        // V tile: unpadded rows, 32-byte units XOR-swizzled by the row
   constexpr int STAGE = KTILE + VTILE;
-  constexpr int KPW = (NKI + 3) / 4;         // K transfers per wave (the last may be missing)
-  constexpr int VPW = (NVI + 3) / 4;         // V transfers per wave
+  constexpr int KPW = NKI / NW;               // K transfers per wave
+  constexpr int VPW = NVI / NW;               // V transfers per wave
   constexpr int RPI = 64 / CPR;              // V rows per transfer
   static_assert(BN * CPR % 64 == 0, "V tile must split into whole wave transfers");
-  static_assert(NKI % 4 == 0 && NVI % 4 == 0 && (KPW == 4 || KPW == 2) && VPW == KPW, "every wave issues the same transfers");
+  static_assert(NKI % NW == 0 && NVI % NW == 0 && (KPW == 4 || KPW == 2) && VPW == KPW, "every wave issues the same transfers");
 
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
 
@@ -227,17 +227,17 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   // which (row, chunk) a lane fetches decides where that chunk lands.  Per lane, the row and chunk of
   // each of this wave's transfers are fixed for the whole kernel.
   // Transfer I covers rows I*RPI .. +RPI-1 of a tile; lane l sits at (row l/CPR, physical chunk l%CPR) and
-  // fetches the logical chunk that the swizzle maps there.  For K the swizzle of row (w + 4t)*RPI + l/CPR
-  // is (4w + l/16) & (CPR-1) for both head sizes, a per-lane constant.
+  // fetches the logical chunk that the swizzle maps there.  Wave w issues the transfers w, w + NW, ...  For K the
+  // swizzle of row (w + NW*t)*RPI + l/CPR is (4w + l/16) & (CPR-1) for both head sizes, a per-lane constant.
   const int v_lrow = l / CPR;
   const int k_chunk = (l % CPR) ^ ((4 * w + (l >> 4)) & (CPR - 1));
-  auto k_slot = [&](int t, int rmax) { return min((w + 4 * t) * RPI + v_lrow, rmax) * pitch_g + k_chunk * 16; };
+  auto k_slot = [&](int t, int rmax) { return min((w + NW * t) * RPI + v_lrow, rmax) * pitch_g + k_chunk * 16; };
   // the 32-byte units of a V row are XOR-swizzled by the row (D = 128: row & 7; D = 64, two rows per 64
   // banks: (row >> 1) & 3), which makes the transposing reads below conflict-free; the row of transfer
-  // w + 4t, lane l is (w + 4t) * RPI + l / CPR, so the swizzle is a per-lane constant
+  // w + NW*t, lane l is (w + NW*t) * RPI + l / CPR, so the swizzle is a per-lane constant
   const int v_swz = D == 128 ? ((4 * (w & 1) + v_lrow) << 1) : (((v_lrow >> 1) & 3) << 1);
   const int v_chunk = (l % CPR) ^ v_swz;
-  auto v_slot = [&](int t, int rmax) { return min((w + 4 * t) * RPI + v_lrow, rmax) * pitch_g + v_chunk * 16; };
+  auto v_slot = [&](int t, int rmax) { return min((w + NW * t) * RPI + v_lrow, rmax) * pitch_g + v_chunk * 16; };
   int k_off[KPW], v_off[VPW];                                // byte offsets inside a tile that is fully cached
 #pragma unroll
   for (int t = 0; t < KPW; ++t) k_off[t] = k_slot(t, BN);
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   for (int t = 0; t < VPW; ++t) v_off[t] = v_slot(t, BN);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(FLUX_LDS char*)smem;
 
-  const uint32_t lds_w = lds0 + 1024 * w;                    // this wave's 1 KB slot inside every 4 KB of a stage
+  const uint32_t lds_w = lds0 + 1024 * w;                    // this wave's 1 KB slot inside every NW KB of a stage
 
   // tile index (in units of BN keys) of iteration `it`: the blocks [0, n_a) first, then [win0, win0 + n_b)
   auto tile_of = [&](int it) { return it < n_a ? it : win0 + (it - n_a); };
@@ -260,10 +260,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     const uint32_t lk = lds_w + stage * STAGE;
 #pragma unroll
     for (int t = 0; t < KPW; ++t)
-      if (4 * t + 3 < NKI || w + 4 * t < NKI) dma16(kt, k_slot(t, rmax), lk + 4096 * t);
+      dma16(kt, k_slot(t, rmax), lk + 1024 * NW * t);
 #pragma unroll
     for (int t = 0; t < VPW; ++t)
-      if (4 * t + 3 < NVI || w + 4 * t < NVI) dma16(vt, v_slot(t, rmax), lk + KTILE + 4096 * t);
+      dma16(vt, v_slot(t, rmax), lk + KTILE + 1024 * NW * t);
   };
 
   // ---- per-lane LDS read offsets (bytes, relative to stage 0; the stage is added as an immediate)
@@ -378,14 +378,14 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
         if ((nxt_kb + 1) * BN <= len) {
           const int64_t off = (int64_t)nxt_kb * step_b;
           if constexpr (KPW == 4) dma_tile4<(STG ^ 1) * STAGE, KTILE>(kbase + off, vbase + off, k_off, v_off, lds_w);
-          else dma_tile2<(STG ^ 1) * STAGE, KTILE>(kbase + off, vbase + off, k_off, v_off, lds_w);
+          else dma_tile2<(STG ^ 1) * STAGE, KTILE, 1024 * NW>(kbase + off, vbase + off, k_off, v_off, lds_w);
         } else {
           issue_tile_clamped(nxt_kb, STG ^ 1);
         }
       }
     } else if (it + 1 < lim_whole) {                         // the next tile, in flight during the math below
       if constexpr (KPW == 4) dma_tile4<(STG ^ 1) * STAGE, KTILE>(kt_n, vt_n, k_off, v_off, lds_w);
-      else dma_tile2<(STG ^ 1) * STAGE, KTILE>(kt_n, vt_n, k_off, v_off, lds_w);
+      else dma_tile2<(STG ^ 1) * STAGE, KTILE, 1024 * NW>(kt_n, vt_n, k_off, v_off, lds_w);
       const int64_t adv = it + 2 == n_a ? jump_b : step_b;   // on to the tile after it (the window part starts at win0)
       kt_n += adv;
       vt_n += adv;
@@ -656,6 +656,14 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.sink_lim = geom.sink_lim;
   a.win_blocks = geom.win_blocks;
   a.blk_shift = geom.shift;
+  // Long prompts at head dimension 128 run with 256 query rows and eight waves per workgroup (one workgroup per CU):
+  // every wave then issues half the tile transfers per block.  Measured: FA launches gain 1-3 % from 16384 tokens
+  // up; SA launches lose 4 % at 16384 tokens (more of a 256-row tile's blocks are cut by the window's start and by the
+  // diagonal), under 1 % at 32768 and nothing at 65536; short prompts lose 4-25 % (fewer, longer workgroups).  Hence
+  // the bound on the longest prompt of the launch, which is all the host knows.  The results are the same bit for
+  // bit.  The block-sparse form keeps 128 rows (its scan handles three query blocks per tile).
+  const bool wide = !bm && cfg.head_dim == 128 && max_q_len >= kPrefillWideMinRows;
+  const int BM = wide ? 256 : 128;
   a.n_qtiles = (max_q_len + BM - 1) / BM;
   a.scale_log2 = scale * kLog2e;
   a.out_fp32 = cfg.out_dtype;
@@ -682,11 +690,12 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   if (n_wg > 0x7FFFFFFFll) return hipErrorInvalidValue;
   const dim3 grid((unsigned)n_wg);
   if (bm) {
-    if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, true>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((prefill_kernel<64, true>), grid, dim3(256), 0, s, a);
+    if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, true, 4>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((prefill_kernel<64, true, 4>), grid, dim3(256), 0, s, a);
   } else {
-    if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, false>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((prefill_kernel<64, false>), grid, dim3(256), 0, s, a);
+    if (wide) hipLaunchKernelGGL((prefill_kernel<128, false, 8>), grid, dim3(512), 0, s, a);
+    else if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, false, 4>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((prefill_kernel<64, false, 4>), grid, dim3(256), 0, s, a);
   }
   return hipGetLastError();
 }

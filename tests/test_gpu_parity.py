@@ -83,13 +83,17 @@ class Layer:
             self.lens[b] += n
             off += n
 
-    def prefill(self, qb, n_q, modes):
+    def prefill(self, qb, n_q, modes, max_q_len=None, want_ref=True):
+        """max_q_len: the host's bound on the longest prompt of the call (default: the longest); a larger bound is
+        valid and chooses the launch shape (from 32768 rows on: 256-row workgroups at head dimension 128)."""
         F = self.F
         t = int(sum(n_q))
         out = torch.full((t, self.hq, self.d), float("nan"), dtype=torch.float32, device="cuda")
-        F.flux_attn_prefill(self.ctx, self.cfg, H.bits_to_torch(qb), cu(n_q), int(max(n_q)), int(max(self.lens)),
-                            self.cache, u8(modes), out)
+        F.flux_attn_prefill(self.ctx, self.cfg, H.bits_to_torch(qb), cu(n_q), int(max_q_len or max(n_q)),
+                            int(max(max_q_len or 0, max(self.lens))), self.cache, u8(modes), out)
         torch.cuda.synchronize()
+        if not want_ref:
+            return out.cpu().numpy(), None
         ref = []
         off = 0
         for b, n in enumerate(n_q):

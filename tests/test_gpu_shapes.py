@@ -1,6 +1,7 @@
 """Seeded sweep over odd shapes through the C ABI against the oracle: group sizes that do not fill an MFMA
 column block, windows shorter than a key tile, no sinks, sinks longer than the prompt, chunk boundaries off
-every tile edge, both head sizes, token-exact and block-granular masks, ragged batches with mixed modes.
+every tile edge, both head sizes, both launch shapes of the prefill kernel, token-exact and block-granular masks,
+ragged batches with mixed modes.
 Every case is small enough for the explicit-mask oracle; the draw is fixed by the case number."""
 import numpy as np
 import pytest
@@ -40,7 +41,8 @@ def test_odd_shapes(F, ctx, case):
     window = int(rng.choice([1, 7, 64, 130, 300]))
     block = int(rng.choice([1, 1, 16, 64]))
     modes = [int(x) for x in rng.integers(0, 2, size=batch)]
-    lay = Layer(F, ctx, 2000 + case, batch, hq, hkv, d, 720, n_sink, window, scales=bool(case % 2), block=block)
+    # (head dimension 128: a cache as large as the bound that chooses the launch shape of long prompts, see below)
+    lay = Layer(F, ctx, 2000 + case, batch, hq, hkv, d, 720 if d == 64 else 32768, n_sink, window, scales=bool(case % 2), block=block)
     # prefill in two chunks with a cut anywhere (possibly empty for some sequences)
     first = [int(rng.integers(0, n + 1)) for n in lens]
     what = f"case {case}: heads {hq}/{hkv} D {d} lens {lens} cut {first} sinks {n_sink} window {window} block {block} modes {modes}"
@@ -51,6 +53,11 @@ def test_odd_shapes(F, ctx, case):
         lay.append(kb, vb, part)
         got, ref = lay.prefill(qb, part, modes)
         H.assert_close(got, ref, what + " prefill")
+        if d == 128:
+            # the launch shape of long prompts (256 query rows and eight waves per workgroup), chosen by the host's
+            # bound on the prompt length, which may be larger than needed: the same results bit for bit
+            wide, _ = lay.prefill(qb, part, modes, max_q_len=32768, want_ref=False)
+            assert np.array_equal(wide, got), what + " prefill, launch shape of long prompts"
     for step in range(2):
         qb, kb, vb = lay.new_tokens([1] * batch)
         lay.append(kb, vb, [1] * batch)

@@ -187,7 +187,7 @@ def main():
             "sa_kernel_tflops": flops_sa / (sa_avg * 1e-3) / 1e12 if sa_ms else None,
         }
         achieved = flops_fa / (fa_avg * 1e-3) / 1e12 if fa_ms else 0.0
-        roofline = {"kernel": "prefill_kernel<128, false, 8> (FA layers; 256 query rows per workgroup from 32768-token prompts on)", "bound": "mfma", "achieved": achieved,
+        roofline = {"kernel": "prefill_kernel<128, false, 8, 2> (FA layers; eight waves per workgroup on two heads of a GQA group from 32768-token prompts on)", "bound": "mfma", "achieved": achieved,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                     "traffic": None, "traffic_note": "not the profiled workload",
                     "traffic_unit": "bytes per launch",

@@ -2,7 +2,8 @@
 // sink + window subset of Sec. 4.1 / App. C.3), chosen per sequence by the cached mode byte.
 //
 // Shape of the computation (one workgroup = 128 query rows of one head, 4 waves x 32 rows = 2 column blocks
-// of 16 queries; launches for long prompts use 8 waves and 256 rows per workgroup, see launch_prefill):
+// of 16 queries; launches for long prompts use 8 waves per workgroup: the same 128 rows of two heads of a GQA
+// group, or 256 rows of one head, see launch_prefill):
 //   for each VISITED 64-key block (FA: all blocks up to the diagonal; SA: the sink blocks and the
 //   blocks that intersect the tile's window, nothing else: hidden blocks are skipped, not masked)
 //     S^T[key][q]  = K[key][:] . Q[q][:]     MFMA 16x16x32 bf16, A = K rows from LDS, B = Q in registers
@@ -91,9 +92,10 @@ __device__ __forceinline__ void dma_tile2(const char* kt, const char* vt, const 
                : "memory", "m0", "scc");
 }
 
-template <int D, bool BS, int NW>   // NW: waves per workgroup, 4 (two workgroups per CU) or 8 (one)
+template <int D, bool BS, int NW, int HP = 1>   // NW: waves per workgroup, 4 (two workgroups per CU) or 8 (one); HP: heads per workgroup
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void prefill_kernel(PrefillArgs a) {
-  constexpr int BM = 32 * NW;             // query rows per workgroup
+  constexpr int RW = NW / HP;             // waves per head
+  constexpr int BM = 32 * RW;             // query rows per workgroup (of each of its heads)
   constexpr int BN = 64;                  // keys per iteration: two halves of 32, the K dimension of one PV MFMA
   constexpr int KC = D / 32;              // MFMA k-steps over the head dimension (QK^T)
   constexpr int DB = D / 16;              // 16-wide output blocks over the head dimension (PV)
@@ -123,7 +125,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void prefill_kernel(Prefi
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
 
   const int tid = threadIdx.x;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave of the workgroup: its share of the tile transfers
+  const int wr = w % RW, hsel = w / RW;                      // its rows within the tile, and which of the workgroup's heads
   const int l = tid & 63;
   const int g = l >> 4, n = l & 15;
   // ---- which (sequence, head, query tile) this workgroup owns.  Workgroups go to the 8 XCDs round-robin
@@ -136,24 +139,30 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void prefill_kernel(Prefi
     const int i = blockIdx.x;
     const int n_pairs = a.batch * a.hkv;
     if (a.xcd_map == 1) {                                    // n_pairs a multiple of 8: pairs x, x+8, ... on XCD x
-      const int x = i & 7, j = i >> 3, per = n_pairs >> 3;
-      const int g = j % a.group, r = (j / a.group) % per, qtd = j / (a.group * per);
+      const int x = i & 7, j = i >> 3;
+      const int gw = a.group / HP;                           // workgroups per (pair, query tile)
+      // An XCD takes its pairs one after the other (all tiles of a pair, heaviest first, the heads of a tile next to
+      // each other).  Interleaving the pairs tile by tile looks more even, but in a ragged batch the tiles past a
+      // short sequence's end are empty workgroups, and at fixed places of a short period they keep falling to the
+      // same CUs (consecutive workgroups go round the CUs of an XCD), leaving the others idle: measured 1.5 - 2 x.
+      const int r = j / (gw * a.n_qtiles), qtd = (j / gw) % a.n_qtiles, g = j % gw;
       const int pair = x + 8 * r;
       b = pair / a.hkv;
-      h = (pair % a.hkv) * a.group + g;
+      h = (pair % a.hkv) * a.group + HP * g + hsel;
       qt = a.n_qtiles - 1 - qtd;
     } else if (a.xcd_map == 2) {                             // n_pairs divides 8: 8 / n_pairs XCDs share a pair
       const int x = i & 7, j = i >> 3, share = 8 / n_pairs;
       const int pair = x % n_pairs, sl = x / n_pairs;
-      const int g = j % a.group, qtd = (j / a.group) * share + sl;
+      const int gw = a.group / HP;
+      const int g = j % gw, qtd = (j / gw) * share + sl;
       b = pair / a.hkv;
-      h = (pair % a.hkv) * a.group + g;
+      h = (pair % a.hkv) * a.group + HP * g + hsel;
       qt = a.n_qtiles - 1 - qtd;
       if (qt < 0) return;                                    // padding of the last round (uniform)
     } else {                                                 // any other shape: plain order, heavy tiles first
       qt = a.n_qtiles - 1 - i % a.n_qtiles;
-      h = (i / a.n_qtiles) % a.hq;
-      b = i / (a.n_qtiles * a.hq);
+      h = HP * ((i / a.n_qtiles) % (a.hq / HP)) + hsel;
+      b = i / (a.n_qtiles * (a.hq / HP));
     }
   }
   const int kvh = h / a.group;
@@ -178,7 +187,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void prefill_kernel(Prefi
   const int r_tile_last = min(qt * BM + BM - 1, n_q - 1);
   const int i_tile_min = pos0 + qt * BM;
   const int i_tile_max = pos0 + r_tile_last;
-  const int r_w0 = qt * BM + 32 * w;
+  const int r_w0 = qt * BM + 32 * wr;
   const int i_w_min = pos0 + r_w0;
   const int i_w_max = pos0 + min(r_w0 + 31, n_q - 1);       // < i_w_min if the wave has no valid row
   const bool wave_active = r_w0 < n_q;
@@ -656,14 +665,18 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   a.sink_lim = geom.sink_lim;
   a.win_blocks = geom.win_blocks;
   a.blk_shift = geom.shift;
-  // Long prompts at head dimension 128 run with 256 query rows and eight waves per workgroup (one workgroup per CU):
-  // every wave then issues half the tile transfers per block.  Measured: FA launches gain 1-3 % from 16384 tokens
-  // up; SA launches lose 4 % at 16384 tokens (more of a 256-row tile's blocks are cut by the window's start and by the
-  // diagonal), under 1 % at 32768 and nothing at 65536; short prompts lose 4-25 % (fewer, longer workgroups).  Hence
-  // the bound on the longest prompt of the launch, which is all the host knows.  The results are the same bit for
-  // bit.  The block-sparse form keeps 128 rows (its scan handles three query blocks per tile).
+  // Long prompts at head dimension 128 run with eight waves per workgroup (one workgroup per CU) that share every K/V
+  // tile, so that each wave issues half the tile transfers per block: waves 0-3 and 4-7 take the same 128 query rows of
+  // two heads of a GQA group (an even group size), else 256 rows of one head.  Measured against the four-wave shape
+  // with 256 rows: FA launches gain 1-3 % from 16384 tokens up; SA launches lose 4 % at 16384 tokens (more of a 256-row
+  // tile's blocks are cut by the window's start and by the diagonal), under 1 % at 32768 and nothing at 65536; short
+  // prompts lose 4-25 % (fewer, longer workgroups).  Two heads on the same rows have one diagonal and one window
+  // start: another 0.2 % on FA and 1 % on SA from 32768 tokens up.  Hence the bound on the longest prompt of the
+  // launch, which is all the host knows.  The results are the same bit for bit.  The block-sparse form keeps four
+  // waves (its scan handles three query blocks per tile).
   const bool wide = !bm && cfg.head_dim == 128 && max_q_len >= kPrefillWideMinRows;
-  const int BM = wide ? 256 : 128;
+  const int HP = wide && a.group % 2 == 0 ? 2 : 1;          // two heads of a group share the workgroup's K/V tiles
+  const int BM = wide && HP == 1 ? 256 : 128;
   a.n_qtiles = (max_q_len + BM - 1) / BM;
   a.scale_log2 = scale * kLog2e;
   a.out_fp32 = cfg.out_dtype;
@@ -678,14 +691,14 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
   long long n_wg;
   if (n_pairs % 8 == 0) {
     a.xcd_map = 1;
-    n_wg = (long long)a.n_qtiles * cfg.n_q_heads * cache.batch;
+    n_wg = (long long)a.n_qtiles * (cfg.n_q_heads / HP) * cache.batch;
   } else if (8 % n_pairs == 0) {
     a.xcd_map = 2;
     const long long share = 8 / n_pairs;
-    n_wg = 8 * a.group * ((a.n_qtiles + share - 1) / share);
+    n_wg = 8 * (a.group / HP) * ((a.n_qtiles + share - 1) / share);
   } else {
     a.xcd_map = 0;
-    n_wg = (long long)a.n_qtiles * cfg.n_q_heads * cache.batch;
+    n_wg = (long long)a.n_qtiles * (cfg.n_q_heads / HP) * cache.batch;
   }
   if (n_wg > 0x7FFFFFFFll) return hipErrorInvalidValue;
   const dim3 grid((unsigned)n_wg);
@@ -693,7 +706,8 @@ hipError_t launch_prefill(const Ctx& c, const flux_attn_cfg& cfg, const void* q,
     if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, true, 4>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((prefill_kernel<64, true, 4>), grid, dim3(256), 0, s, a);
   } else {
-    if (wide) hipLaunchKernelGGL((prefill_kernel<128, false, 8>), grid, dim3(512), 0, s, a);
+    if (wide && HP == 2) hipLaunchKernelGGL((prefill_kernel<128, false, 8, 2>), grid, dim3(512), 0, s, a);
+    else if (wide) hipLaunchKernelGGL((prefill_kernel<128, false, 8>), grid, dim3(512), 0, s, a);
     else if (cfg.head_dim == 128) hipLaunchKernelGGL((prefill_kernel<128, false, 4>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((prefill_kernel<64, false, 4>), grid, dim3(256), 0, s, a);
   }

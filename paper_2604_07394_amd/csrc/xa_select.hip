@@ -84,8 +84,10 @@ __global__ __launch_bounds__(256, 2) void xa_select_kernel(XaArgs a) {
     const int i = blockIdx.x;
     const int hkv = a.hq / a.group, n_pairs = a.batch * hkv;
     if ((n_pairs & 7) == 0) {
-      const int x = i & 7, j = i >> 3, per = n_pairs >> 3;
-      const int gh = j % a.group, r = (j / a.group) % per, gd = j / (a.group * per);
+      const int x = i & 7, j = i >> 3;
+      // (the XCD's pairs one after the other, not interleaved group by group: the groups past a short sequence's end
+      // are empty workgroups, and at fixed places of a short period they would keep falling to the same CUs)
+      const int r = j / (a.group * a.n_groups), gd = (j / a.group) % a.n_groups, gh = j % a.group;
       const int pair = x + 8 * r;
       b = pair / hkv;
       h = (pair % hkv) * a.group + gh;

@@ -130,10 +130,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void prefill_kernel(Prefi
   const int l = tid & 63;
   const int g = l >> 4, n = l & 15;
   // ---- which (sequence, head, query tile) this workgroup owns.  Workgroups go to the 8 XCDs round-robin
-  // by linear id, and each XCD has its own L2.  All query heads and query tiles that read one
-  // (sequence, KV head) pair are therefore given ids of one residue mod 8, heaviest tiles first and the
-  // heads of a group next to each other, so that the workgroups resident on an XCD walk the same K/V
-  // rows at the same time and the rows come from HBM once per XCD instead of once per workgroup.
+  // by linear id, and each XCD has its own L2.  The workgroups that an XCD holds at one time are therefore
+  // given neighbouring query tiles of one (sequence, KV head) pair, heaviest tiles first and the heads of a
+  // group next to each other, so that they walk the same K/V rows at the same time and the rows come from
+  // HBM once per XCD and round instead of once per workgroup.
   int qt, h, b;
   {
     const int i = blockIdx.x;
@@ -145,8 +145,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void prefill_kernel(Prefi
       // each other).  Interleaving the pairs tile by tile looks more even, but in a ragged batch the tiles past a
       // short sequence's end are empty workgroups, and at fixed places of a short period they keep falling to the
       // same CUs (consecutive workgroups go round the CUs of an XCD), leaving the others idle: measured 1.5 - 2 x.
-      const int r = j / (gw * a.n_qtiles), qtd = (j / gw) % a.n_qtiles, g = j % gw;
-      const int pair = x + 8 * r;
+      // Two rotations even out work that differs between heads (block-sparse launches whose heads keep different
+      // shares), at no cost where it does not: the heads of a tile change places from tile to tile, so that a CU
+      // (which sees every 32nd workgroup of its XCD) meets all heads of the group; and the eight pairs of a round
+      // change XCD every 16 tiles (one round of resident workgroups), so that every XCD works through two rounds of
+      // every pair instead of all rounds of one.  A round streams its K/V rows from behind the L2 anyway.
+      const int r = j / (gw * a.n_qtiles), qtd = (j / gw) % a.n_qtiles, g = (j + qtd) % gw;
+      const int pair = ((x + qtd / 16) & 7) + 8 * r;
       b = pair / a.hkv;
       h = (pair % a.hkv) * a.group + HP * g + hsel;
       qt = a.n_qtiles - 1 - qtd;

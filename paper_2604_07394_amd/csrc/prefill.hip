@@ -138,7 +138,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void prefill_kernel(Prefi
   {
     const int i = blockIdx.x;
     const int n_pairs = a.batch * a.hkv;
-    if (a.xcd_map == 1) {                                    // n_pairs a multiple of 8: pairs x, x+8, ... on XCD x
+    if (a.xcd_map == 1) {                                    // n_pairs a multiple of 8: eight pairs at a time, one per XCD
       const int x = i & 7, j = i >> 3;
       const int gw = a.group / HP;                           // workgroups per (pair, query tile)
       // An XCD takes its pairs one after the other (all tiles of a pair, heaviest first, the heads of a tile next to

@@ -131,8 +131,8 @@ int flux_kv_append(flux_ctx* ctx, const flux_kv_cache* cache, int n_kv_heads, in
  * out dev [T, n_q_heads, head_dim] in cfg->out_dtype.  max_q_len, max_kv_len: host upper bounds
  * on n_q(b) and kv_len[b] (they size the launch; larger than needed is valid, smaller truncates
  * nothing: rows beyond max_q_len are not computed; a bound far above the real lengths costs empty
- * workgroups, and from 32768 on it selects the launch shape tuned for long prompts, with the same
- * results bit for bit).  SA tiles that the mask hides are skipped,
+ * workgroups, and max_q_len from 32768 on (or from 16384 on with max_kv_len from 32768 on) selects
+ * the launch shape tuned for long prompts, with the same results bit for bit).  SA tiles that the mask hides are skipped,
  * not masked: their K/V rows are never read.  A 64-key tile that is partly visible is read whole
  * (up to kv_len[b]), so the cached rows below kv_len[b] must hold finite values.  If the device finds n_q(b) > kv_len[b] (the caller did not append first), only the first
  * kv_len[b] query rows of that sequence are computed and FLUX_DEV_BAD_LENGTH is raised. */

@@ -289,6 +289,28 @@ def main():
             prefill["blocksparse"] = bs
             del keep, xa_keep, tri, eye, band
 
+            # ---- one FA launch on a ragged batch with a small GQA group (16/8 heads, prompts of 8192 and 65536 tokens):
+            # most workgroups past the short prompt's end are empty, and where they fall among the others decides whether
+            # every CU gets work (the launch order takes the pairs of an XCD one after the other for this reason)
+            if not args.small:
+                rl, rhq = [8192, 65536], 16
+                rt = sum(rl)
+                rcfg = F.attn_cfg(rhq, HKV, D, NS, W, 0.0, 0)
+                rq = torch.empty(1, rt, rhq, D, dtype=torch.bfloat16, device=dev)
+                rk = torch.empty(1, rt, HKV, D, dtype=torch.bfloat16, device=dev)
+                synth_gpu.fill_normal_bf16(rq, SEED + 91, synth.stream_id(synth.STREAM_Q))
+                synth_gpu.fill_normal_bf16(rk, SEED + 91, synth.stream_id(synth.STREAM_K))
+                rcache = F.KVCache.empty(len(rl), HKV, max(rl), D)
+                rcu = torch.tensor(np.concatenate([[0], np.cumsum(rl)]), dtype=torch.int32, device=dev)
+                F.flux_kv_append(ctx, rcache, HKV, D, rk[0], rk[0], rcu, rt, max(rl))
+                rout = torch.empty(rt, rhq, D, dtype=torch.bfloat16, device=dev)
+                rmode = torch.ones(len(rl), dtype=torch.uint8, device=dev)
+                ms = timed(lambda: F.flux_attn_prefill(ctx, rcfg, rq[0], rcu, max(rl), max(rl), rcache, rmode, rout))
+                rflops = 4.0 * D * rhq * sum(n * (n + 1) // 2 for n in rl)
+                prefill["ragged_small_group_fa"] = {"workload": "one FA launch, batch of 2 prompts (8192 and 65536 tokens), 16/8 heads, D 128",
+                                                    "kernel_ms": ms, "tflops": rflops / (ms * 1e-3) / 1e12}
+                del rq, rk, rcache, rout
+
         # ---- CPU oracle on a bounded sample of the same workload (rank 0, N = 1)
         if not args.no_cpu_baseline:
             from oracle import flux_oracle as O

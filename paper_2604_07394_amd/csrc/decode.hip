@@ -360,9 +360,9 @@ __global__ __launch_bounds__(256) void decode_splitk_kernel(DecodeArgs a) {
   const int k_lane = n * (int)a.stride_t + 8 * g;           // element offsets inside a block of consecutive rows
   const int v_lane = (l / CPR) * (int)a.stride_t + (l % CPR) * 8;
 
-  // When the rows of one call exceed the last-level cache they are read once and evicted before the next
-  // step: NT selects nontemporal loads, which measurably raise the streaming rate of this access shape
-  // (6.2 -> 7.1 TB/s in isolation).  Short visible lists (an SA layer) keep ordinary loads.
+  // Rows that are read once and evicted before the next step (the launcher decides by the bytes of the call) are
+  // fetched with nontemporal loads (NT), which measurably raise the streaming rate of this access shape
+  // (6.2 -> 7.1 TB/s in isolation).
   auto ld = [](const u32x4* p) -> u32x4 { return NT ? __builtin_nontemporal_load(p) : *p; };
   u32x4 kreg[2][KC], vreg[VL];
   auto load_block = [&](int p0) {                           // p0 is wave-uniform
@@ -592,8 +592,11 @@ hipError_t launch_decode(const Ctx& c, const flux_attn_cfg& cfg, const void* q, 
   a.partials = c.partials + plan.table_floats;
   a.status = c.status;
   const dim3 grid(plan.units);
-  // K and V bytes one call may read, against the 256 MB last-level cache
-  const bool nt = 4.0 * cache.batch * cfg.n_kv_heads * cfg.head_dim * (double)max_kv_len > 256.0 * 1024 * 1024;
+  // K and V bytes one call may read.  A call of a model whose layers together stream more than the 256 MB last-level
+  // cache finds none of its rows there, whatever its own size (an SA layer reads 138 MB of a 4 GB cache): from 64 MB
+  // on the rows are fetched with nontemporal loads (SA layer 34.5 -> 33.4 us, FA layers as before); smaller calls are
+  // bound by their launches either way.
+  const bool nt = 4.0 * cache.batch * cfg.n_kv_heads * cfg.head_dim * (double)max_kv_len > 64.0 * 1024 * 1024;
   if (fused) {
     if (cfg.head_dim == 128) {
       if (nt) hipLaunchKernelGGL((decode_splitk_kernel<128, true, true>), grid, dim3(256), 0, s, a);
